@@ -71,6 +71,14 @@ __device__ __forceinline__ unsigned long long read_lane64(unsigned long long v, 
 __device__ __forceinline__ void pin_here(uint32_t& v) { asm volatile("" : "+v"(v) : : "memory"); }
 __device__ __forceinline__ void pin_here(unsigned long long& v) { asm volatile("" : "+v"(v) : : "memory"); }
 
+// Wait until every vector-memory operation this wavefront has issued is complete: loads have
+// returned, stores and atomics have been acknowledged by the L2 of this XCD.  A workgroup-scope
+// fence does NOT do this on gfx950 (all wavefronts of a workgroup share one L2, so the compiler
+// emits no wait for it, and none at a barrier either): wherever a barrier is followed by a count,
+// a flag or a write-back that speaks for the stores of the whole workgroup, every wavefront runs
+// this wait before the barrier.
+__device__ __forceinline__ void wait_vm_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Hyper-parameters as the kernel sees them.  Whether weight decay takes part is
 // a compile-time property of the kernel: a run-time test between the loads and
 // the arithmetic of every vector was measured to cost 12 % of the stream's
@@ -778,9 +786,10 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
         a.hs->t_sel_enter = wall_clock64();
         a.hs->t_sel_first_pub = 0;
     }
-    // Memory ordering.  A store's acknowledgement (what a workgroup-scope fence waits for) only
-    // says that the store has reached the L2 of the issuing XCD; other XCDs see it once that L2
-    // has written it back, and only an agent-scope release fence waits for that (measured: a
+    // Memory ordering.  A store's acknowledgement (what `s_waitcnt vmcnt(0)` waits for; a
+    // workgroup-scope fence waits for nothing here) only says that the store has reached the L2
+    // of the issuing XCD; other XCDs see it once that L2 has written it back, and only an
+    // agent-scope release fence waits for that (measured: a
     // flag stored after acknowledged write-through stores is seen by other workgroups before
     // the data).  So the selector raises `published` behind an agent-scope release fence -- one
     // L2 write-back per selection step.  The bitmap, the layer states and the selector's
@@ -812,6 +821,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             ctl->cur_next = ctl->cur_left = 0u;
         }
     }
+    wait_vm_done();                     // the cleared counts are in the L2 before anybody can add to them
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
 
@@ -938,6 +948,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                 }
                 st.marks_applied += static_cast<uint32_t>(n_new);
                 folded_now = true;
+                if (!in_lds) wait_vm_done();                              // a bitmap in memory: the ORs have been performed
                 __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the ORs have landed
             }
             // a short first step gets the workers going; later steps amortise the publication
@@ -982,6 +993,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                         }
                         fold_lanes(a, bm, ls, rel, l, st);
                         st.pending -= static_cast<uint32_t>(__popcll(__ballot(rel)));
+                        if (!in_lds) wait_vm_done();
                         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
                     }
                     next = wave_min_i64(next);
@@ -1209,7 +1221,8 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             __hip_atomic_store(q + 3, (static_cast<unsigned long long>(t0 + static_cast<uint32_t>(c)) << 32) | t0,
                                __ATOMIC_RELAXED, P3_AGENT);
         }
-        // every thread's record stores have reached this XCD's L2 ...
+        // every wavefront's record stores have reached this XCD's L2 ...
+        wait_vm_done();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (wave == 0) {
@@ -1281,6 +1294,9 @@ struct QueueCtx {
     const P3Run* runq;
     P3HostShared* hs;
     uint64_t watchdog_ticks;
+    int64_t arena_elems;
+    int32_t L;
+    int32_t tile_elems;
 };
 
 struct Located {
@@ -1331,6 +1347,7 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
             const uint32_t upto = pub - r_have > P3_RUN_CACHE ? r_have + P3_RUN_CACHE : pub;
             for (uint32_t base = r_have; base < upto; base += 64u) {
                 const uint32_t r = base + static_cast<uint32_t>(lane);
+                bool bad = false;
                 if (r < upto) {
                     const unsigned long long* q = reinterpret_cast<const unsigned long long*>(&a.runq[r]);
                     const unsigned long long q0 = __hip_atomic_load(q, __ATOMIC_RELAXED, P3_AGENT);
@@ -1345,6 +1362,15 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
                     e.tile0 = static_cast<uint32_t>(q3 & 0xffffffffull);
                     e.tile_end = static_cast<uint32_t>(q3 >> 32);
                     ring[r & (P3_RUN_CACHE - 1)] = e;
+                    bad = !p3_run_valid(e, a.arena_elems, a.L, a.tile_elems);
+                }
+                if (__ballot(bad) != 0ull) {
+                    // a record the selector cannot have written (it would be turned into addresses): the
+                    // workgroup takes no more work and the drain is reported as failed
+                    if (lane_is(lane, 0)) a.hs->worker_status = P3D_OVERFLOW;
+                    out.r_next = r_next;
+                    out.r_have = r_have;
+                    return out;
                 }
             }
             r_have = upto;
@@ -1367,20 +1393,6 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
     out.r_next = r_next;
     out.r_have = r_have;
     return out;
-}
-
-// Tile k of the queue, given the run that holds it: grid cell (k - tile0) of the run, clipped.
-__device__ __forceinline__ P3TileDesc tile_of_run(const P3Run& r, uint32_t k, int32_t tile_elems) {
-    const int64_t cell_lo = (r.start - r.grid_off) + static_cast<int64_t>(k - r.tile0) * tile_elems;
-    const int64_t cell_hi = cell_lo + tile_elems;
-    const int64_t end = r.start + r.len;
-    const int64_t lo = cell_lo > r.start ? cell_lo : r.start;
-    const int64_t hi = cell_hi < end ? cell_hi : end;
-    P3TileDesc d;
-    d.start = lo;
-    d.n = static_cast<int32_t>(hi - lo);
-    d.layer = r.layer;
-    return d;
 }
 
 // The worker loop.  WAIT = true: the selector runs concurrently in workgroup 0
@@ -1417,7 +1429,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
     P3Ctl* ctl = a.ctl;
     const HyperT<WD> h = {a.lr, a.mu, a.rescale, a.wd};
     const uint64_t t_enter = wall_clock64();
-    const QueueCtx qc = {a.ctl, a.runq, a.hs, a.watchdog_ticks};
+    const QueueCtx qc = {a.ctl, a.runq, a.hs, a.watchdog_ticks, a.arena_elems, a.L, a.tile_elems};
     const FlushCtx fc = {a.ctl, a.layer_req, a.t_seen_dev, a.t_seen, a.t_done, a.done_flag, a.iter_seq, a.L};
     const int xcd = xcd_of_this_wave();
 
@@ -1446,7 +1458,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
             cur.layer = uni(f.run.layer);
             cur.tile0 = uni(f.run.tile0);
             cur.tile_end = uni(f.run.tile_end);
-            d0 = tile_of_run(cur, k, a.tile_elems);
+            d0 = p3_tile_of_run(cur, k, a.tile_elems);
         }
         if (lane_is(lane, 0)) s_desc = d0;
     }
@@ -1474,7 +1486,8 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
             if (lane_is(lane, 0)) tk_pre = __hip_atomic_fetch_add(&ctl->ticket, 1u, __ATOMIC_RELAXED, P3_AGENT);
             fv_pre = load_flush_view(ctl, xcd);
         }
-        // the write-through stores of this thread have been acknowledged
+        // the write-through stores of this wavefront have been acknowledged (they are in this XCD's L2)
+        wait_vm_done();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();                                      // everyone's stores are out: the tile may be retired
 
@@ -1549,7 +1562,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
             dn.start = 0;
             dn.n = P3T_END;
             dn.layer = 0;
-            if (found) dn = tile_of_run(cur, k, a.tile_elems);
+            if (found) dn = p3_tile_of_run(cur, k, a.tile_elems);
             if (lane_is(lane, 0)) s_desc = dn;                // everyone has read the old one before the barrier above
         }
         __syncthreads();                                      // the next descriptor is in LDS

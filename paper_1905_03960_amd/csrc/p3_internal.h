@@ -5,6 +5,8 @@
 
 #include <stdint.h>
 
+#include "p3_tiles.h"
+
 #define P3_BLOCK 832            // threads per workgroup = 13 wavefronts of 64, one workgroup per CU (measured optimum
                                 // with the arenas well placed: 704 lanes 1.067 ms, 768 1.032, 832 1.020, 896 1.035, 960 1.045)
 #define P3_WAVES (P3_BLOCK / 64)
@@ -39,32 +41,6 @@ struct P3LayerDev {
     int32_t count;   // number of slices
     int64_t elems;   // parameters of the layer
 };
-
-// The work queue holds RUNS.  Slices that were claimed in one selection step,
-// belong to one layer and follow each other in memory form a run; the claim
-// order is the order of the runs and, inside a run, of the addresses.  A run is
-// processed as tiles: the cells of a grid of tile_elems elements laid over the
-// arena, clipped to the run (so a tile may span the boundary of two slices of the
-// run -- neighbours in the claim order -- and every tile but a run's first starts
-// on a multiple of tile_elems).  Tiles are numbered through the whole queue;
-// a worker draws a tile number and finds its run in a copy of the run table
-// that its workgroup keeps in LDS, so a tile costs no queue access at all.
-struct P3Run {
-    int64_t start;        // element offset into the arenas
-    int64_t len;          // elements
-    int32_t grid_off;     // start - (start / tile_elems) * tile_elems
-    int32_t layer;        // owning layer
-    uint32_t tile0;       // number of the run's first tile
-    uint32_t tile_end;    // tile0 + tiles of the run
-};
-
-// What a workgroup works on in one round (LDS only).
-struct P3TileDesc {
-    int64_t start;        // element offset into the arenas
-    int32_t n;            // elements, or P3T_END
-    int32_t layer;        // owning layer
-};
-enum { P3T_END = -1 };
 
 #define P3_RUN_CACHE 512    // run records a workgroup keeps in LDS (a ring; power of two)
 #define P3_LDS_BM_WORDS 4096   // the selector keeps the ready bitmap in LDS when it has at most this many words (262,144 slices)
@@ -155,6 +131,7 @@ struct P3DrainArgs {
     float* w;
     float* m;
     // sizes
+    int64_t arena_elems;          // elements of every arena: no run may reach beyond
     int32_t K;
     int32_t L;
     int32_t n_words;

@@ -801,6 +801,7 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
     a.t_done = p->t_done;
     a.w = p->w;
     a.m = p->m;
+    a.arena_elems = p->arena;
     a.K = p->K;
     a.L = p->L;
     a.n_words = (p->K + 63) / 64;
@@ -881,10 +882,12 @@ int p3_sync(p3_plan_t* p, int32_t timeout_ms) {
             reinterpret_cast<std::atomic<uint32_t>*>(&p->done_flag[l])->load(std::memory_order_acquire) == p->iter_seq)
             p->t_seen_done_ns[l] = t;
     if (timed_out) return P3_ERR_TIMEOUT;
+    // an inconsistency the kernel found in its own bookkeeping (selector) or in a queue record (worker)
+    if (p->hs->last_iter == p->iter_seq && (p->hs->last_status == P3D_OVERFLOW || p->hs->worker_status == P3D_OVERFLOW))
+        return P3_ERR_DEVICE;
     if (p->live_issued && p->hs->last_iter == p->iter_seq &&
         (p->hs->last_status != P3D_OK || p->hs->last_claimed != static_cast<uint32_t>(p->K)))
-        return p->hs->last_status == P3D_OVERFLOW ? P3_ERR_DEVICE : P3_ERR_INCOMPLETE;
-    if (p->hs->last_iter == p->iter_seq && p->hs->last_status == P3D_OVERFLOW) return P3_ERR_DEVICE;
+        return P3_ERR_INCOMPLETE;
     if (p->hs->last_iter == p->iter_seq && (p->hs->last_status != P3D_OK || p->hs->worker_status != P3D_OK))
         return P3_ERR_INCOMPLETE;     // a snapshot/ticked drain was stopped by abort or its watchdog
     return P3_OK;

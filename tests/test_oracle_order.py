@@ -233,3 +233,62 @@ def test_fifo_comparison_policy_ties_follow_backward_order():
     p = OraclePlan([2, 2], 1)
     order, _ = p.order_ticked_fifo([0, 0])
     assert list(order) == [2, 3, 0, 1]
+
+
+# ------------- first come, first served: release order other than backward order --
+def test_fifo_hand_worked_cases(golden_dir):
+    """Non-monotone release ticks, an idle server in between, and a backlog in which a layer
+    released later (but before the server is free) waits its turn: Sec. 3's aggressive
+    synchronisation, layers whole in the order backward hands them over."""
+    g = read_golden(os.path.join(golden_dir, "fifo_hand_cases.txt"))
+    p = OraclePlan(g["layer_sizes"], g["slice_elems"][0])
+    for case in "ab":
+        order, tick = p.order_ticked_fifo(g[f"{case}_release_ticks"])
+        assert list(order) == g[f"{case}_fifo_order"], case
+        assert list(tick) == g[f"{case}_claim_ticks"], case
+    p = OraclePlan(g["c_layer_sizes"], g["slice_elems"][0])
+    order, tick = p.order_ticked_fifo(g["c_release_ticks"])
+    assert list(order) == g["c_fifo_order"] and list(tick) == g["c_claim_ticks"]
+
+
+def brute_force_fifo(sizes, S, release):
+    """Independent restatement as a tick-by-tick simulation of a waiting line: at every tick the
+    layers released at that tick join the line (later layer first among them, as backward
+    produces them); the server, when free, takes the head of the line and is busy one tick per
+    slice.  Returns (slice ids in service order, tick at which each was served)."""
+    ids, g = [], 0
+    for n in sizes:
+        k = -(-n // S)
+        ids.append(list(range(g, g + k)))
+        g += k
+    line, out, ticks = [], [], []
+    todo = sum(1 for r in release if r >= 0)
+    in_service = []                                   # slices of the layer being served, not yet served
+    t = 0
+    while todo or line or in_service:
+        for l in sorted((l for l, r in enumerate(release) if r == t), reverse=True):
+            line.append(l)
+            todo -= 1
+        if not in_service and line:
+            in_service = list(ids[line.pop(0)])
+        if in_service:
+            out.append(in_service.pop(0))
+            ticks.append(t)
+        t += 1
+    return out, ticks
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_fifo_order_equals_brute_force(seed):
+    rng = np.random.default_rng(1000 + seed)
+    L = int(rng.integers(1, 9))
+    sizes = [int(x) for x in rng.integers(1, 40, size=L)]
+    S = int(rng.integers(1, 12))
+    # spans longer than the work (idle gaps), shorter (backlog), and equal ticks
+    release = [int(x) for x in rng.integers(0, [4, 30, 120][seed % 3], size=L)]
+    if seed % 4 == 0 and L > 1:
+        release[int(rng.integers(0, L))] = -1            # a layer that is never released
+    p = OraclePlan(sizes, S)
+    order, tick = p.order_ticked_fifo(release)
+    want, want_ticks = brute_force_fifo(sizes, S, release)
+    assert list(order) == want and list(tick) == want_ticks
