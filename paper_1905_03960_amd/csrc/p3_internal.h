@@ -17,6 +17,9 @@
 #define P3_RETIRE_BATCH 4           // tiles of one layer a workgroup finishes before it adds them to the layer's count
 #define P3_PUBLISHED 0x80000000u   // layer_req: the layer's done flag has been written
 #define P3_FLUSH_GAP_TICKS 5000u   // busy workgroups leave 50 us (100 MHz clock) between two write-backs of one L2
+#ifndef P3_EARLY_BELOW_TILES_PER_WG
+#define P3_EARLY_BELOW_TILES_PER_WG 48   // drains of fewer tiles per workgroup draw their tile numbers before the wait for the stores
+#endif
 #define P3_INLINE_MARKS 256      // marks handed to a SNAPSHOT/TICKED drain with its launch arguments
 
 // Device-side status of a drain (written to pinned host memory at its end).
