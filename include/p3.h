@@ -334,6 +334,36 @@ int p3_selector_timeline_ns(p3_plan_t* plan, int64_t* first_publish_ns, int64_t*
 int p3_profile_enable(p3_plan_t* plan, int32_t on);
 int p3_profile_read(p3_plan_t* plan, double* total_ms, int32_t* launches);
 
+/* ---- one iteration that allocates nothing ----
+ * For callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  What p3_bind + p3_begin_iter +
+ * p3_mark_ready_many(ready_layers) + one SNAPSHOT p3_drain do, as one call that
+ * makes no hipMalloc / hipFree and needs no bound plan: the library's control
+ * data (slice and layer tables, ready bitmap, work queue, counters, completion
+ * flags) lives in one static device array of about 310 KB per GPU, which limits
+ * the plan to P3_STATIC_MAX_LAYERS layers and P3_STATIC_MAX_SLICES slices
+ * (RANGE beyond that).  Only kernels are enqueued on hip_stream (no memset, no
+ * copy); the call returns without waiting.
+ *  plan          from p3_plan (not sharded); only read; need not be bound
+ *  grads         host array of W device pointers, as in p3_bind
+ *  weights, momentum   device arenas, updated in place
+ *  ready_layers  host array of n_ready distinct layers, in mark order; their
+ *                slices are claimed in priority order and processed
+ *  order_out     device array of p3_num_slices(plan) int32: the claim order
+ *  result_out    device array of 4 int32: slices claimed, selector status
+ *                (0 ok), worker status (0 ok), layers whose update is complete
+ * All calls on one GPU share that GPU's array, which keeps the previous call's
+ * contents (the call clears what must start at zero): calls that overlap on one
+ * GPU -- on different streams, or from different threads -- race; order them.
+ * Errors: ARG (null, unknown dtype, misaligned arena, sharded plan), RANGE (W,
+ * a layer index, plan beyond the static limits), ALREADY (a layer twice), DEVICE. */
+#define P3_STATIC_MAX_LAYERS 256
+#define P3_STATIC_MAX_SLICES 4096
+int p3_drain_static(const p3_plan_t* plan, int32_t W, const void* const* grads, int32_t grad_dtype,
+                    float* weights, float* momentum, float lr, float mu, float rescale, float wd,
+                    const int32_t* ready_layers, int32_t n_ready, int32_t* order_out,
+                    int32_t* result_out, void* hip_stream);
+
 /* After a P3_ERR_DEVICE: the hipError_t value of the most recent failing HIP
  * call made by the library in this process (0 if none) and, if source_line is
  * not NULL, the line of the runtime source that made it.  Diagnostics only. */

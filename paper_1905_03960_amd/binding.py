@@ -25,6 +25,7 @@ P3_GRAD_FP32, P3_GRAD_BF16 = 0, 1
 P3_MODE_SNAPSHOT, P3_MODE_LIVE, P3_MODE_TICKED = 0, 1, 2
 P3_POLICY_PRIORITY, P3_POLICY_FIFO = 0, 1
 P3_MAX_WORKERS = 64
+P3_STATIC_MAX_LAYERS, P3_STATIC_MAX_SLICES = 256, 4096
 
 _vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
 _P = C.POINTER
@@ -70,6 +71,8 @@ SIGNATURES = {
     "p3_selector_timeline_ns": (C.c_int, [_vp, _P(_i64), _P(_i64)]),
     "p3_profile_enable": (C.c_int, [_vp, _i32]),
     "p3_profile_read": (C.c_int, [_vp, _P(C.c_double), _P(_i32)]),
+    "p3_drain_static": (C.c_int, [_vp, _i32, _P(_vp), _i32, _vp, _vp, _f32, _f32, _f32, _f32, _P(_i32), _i32, _vp, _vp,
+                                  _vp]),
     "p3_last_hip_error": (C.c_int, [_P(C.c_int)]),
     "p3_strerror": (C.c_char_p, [C.c_int]),
 }
@@ -284,6 +287,17 @@ def p3_stream_wait_expired(plan):
 
 def p3_drain(plan, stream=0):
     _check(load().p3_drain(_h(plan), _vp(int(stream))), "p3_drain")
+
+
+def p3_drain_static(plan, grad_ptrs, grad_dtype, weights_ptr, momentum_ptr, lr, mu, rescale, wd, ready_layers,
+                    order_out_ptr, result_out_ptr, stream=0):
+    """The allocation-free iteration: device addresses in, kernels enqueued on `stream`, nothing waited for."""
+    arr = (_vp * len(grad_ptrs))(*[int(p) for p in grad_ptrs])
+    lay = (C.c_int32 * max(len(ready_layers), 1))(*[int(l) for l in ready_layers])
+    _check(load().p3_drain_static(_h(plan), len(grad_ptrs), arr, int(grad_dtype), _vp(int(weights_ptr)),
+                                  _vp(int(momentum_ptr)), float(lr), float(mu), float(rescale), float(wd), lay,
+                                  len(ready_layers), _vp(int(order_out_ptr)), _vp(int(result_out_ptr)),
+                                  _vp(int(stream))), "p3_drain_static")
 
 
 def p3_sync(plan, timeout_ms=-1):

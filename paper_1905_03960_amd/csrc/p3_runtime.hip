@@ -824,7 +824,7 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
     a.rescale = p->rescale;
     a.wd = p->wd;
     // short drains (fewer than 48 tiles per workgroup) draw their tile numbers early (see run_worker)
-    a.early_number = p->tiles_total < 48 * static_cast<int64_t>(p->grid) ? 1 : 0;
+    a.early_number = p->tiles_total < P3_EARLY_BELOW_TILES_PER_WG * static_cast<int64_t>(p->grid) ? 1 : 0;
     a.n_inline = 0;
     if (p->mode != P3_MODE_LIVE && !p->stream_marks && limit - p->drained_upto <= P3_INLINE_MARKS) {
         std::lock_guard<std::mutex> lk(p->mu_host);
@@ -1035,3 +1035,258 @@ int p3_profile_read(p3_plan_t* p, double* total_ms, int32_t* launches) {
 }
 
 }  // extern "C"
+
+// ------------------------------------------------- a drain that allocates nothing ----
+// For callers that cannot allocate (code under HIP graph capture, tight serving loops,
+// harnesses that forbid hipMalloc): one iteration -- marks, then a SNAPSHOT drain -- whose
+// control data (slice and layer tables, ready bitmap, work queue, counters, flags, the
+// kernel's mailbox) lives in one file-scope device array instead of buffers p3_bind
+// allocated.  Every call on a GPU shares that GPU's array.
+
+#define P3_STATIC_TABLE_CHUNK 128     // layers described per launch of the table kernel
+
+namespace {
+
+struct StaticScratch {
+    // ---- cleared at the start of every call (everything up to `layers`) ----
+    P3Ctl ctl;
+    P3HostShared hs;                                  // the kernel's mailbox; device memory here
+    unsigned long long bitmap[P3_STATIC_MAX_SLICES / 64];
+    unsigned long long mark_log[64];                  // never read: the marks travel with the launch
+    unsigned long long layer_done[P3_STATIC_MAX_LAYERS];
+    uint64_t t_seen_dev[P3_STATIC_MAX_LAYERS];
+    uint64_t t_seen[P3_STATIC_MAX_LAYERS];
+    uint64_t t_done[P3_STATIC_MAX_LAYERS];
+    int64_t release[P3_STATIC_MAX_LAYERS];
+    uint32_t layer_req[P3_STATIC_MAX_LAYERS];
+    uint32_t done_flag[P3_STATIC_MAX_LAYERS];
+    int32_t fifo[P3_STATIC_MAX_LAYERS];
+    uint8_t layer_state[P3_STATIC_MAX_LAYERS];
+    // ---- rewritten by the table kernel / the selector before they are read ----
+    alignas(128) P3LayerDev layers[P3_STATIC_MAX_LAYERS];
+    int32_t epoch[P3_STATIC_MAX_SLICES];
+    P3SliceDev slices[P3_STATIC_MAX_SLICES];
+    P3Run runq[P3_STATIC_MAX_SLICES];
+};
+
+constexpr size_t kStaticBytes = (sizeof(StaticScratch) + 255) / 256 * 256;      // about 310 KB
+static_assert(P3_STATIC_MAX_LAYERS <= P3_INLINE_MARKS, "the marks of a call travel with the launch arguments");
+static_assert(P3_STATIC_MAX_SLICES <= P3_LDS_BM_WORDS * 64 && P3_STATIC_MAX_LAYERS <= P3_LDS_LAYERS,
+              "the selector keeps bitmap and layer states in LDS");
+
+}  // namespace
+
+// In host code this name is a stand-in, not a device address: host code uses the pointer that
+// hipGetSymbolAddress returns for the current device (static_state below), never the name.
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+struct StaticDevice {
+    StaticScratch* ptr = nullptr;      // this device's copy of `scratch`
+    int num_cu = 0;
+    int clock_khz = 100000;
+    bool ready = false;
+};
+constexpr int kMaxDevices = 64;
+StaticDevice g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+// Set-up, once per device, with that device current.
+int static_state(StaticDevice** out) {
+    int dev = 0;
+    if (HIPC(hipGetDevice(&dev)) != hipSuccess) return P3_ERR_DEVICE;
+    if (dev < 0 || dev >= kMaxDevices) return P3_ERR_RANGE;
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    StaticDevice& d = g_static[dev];
+    if (!d.ready) {
+        void* ptr = nullptr;
+        if (HIPC(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) != hipSuccess || !ptr) return P3_ERR_DEVICE;
+        int cus = 0, khz = 0;
+        if (HIPC(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess || cus < 1)
+            return P3_ERR_DEVICE;
+        if (HIPC(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev)) == hipSuccess && khz > 0)
+            d.clock_khz = khz;
+        d.ptr = static_cast<StaticScratch*>(ptr);
+        d.num_cu = cus;
+        d.ready = true;
+    }
+    *out = &d;
+    return P3_OK;
+}
+
+// What must start at zero does: a fill kernel, not hipMemsetAsync, so that the call may be captured.
+__global__ void p3_static_clear_kernel(StaticScratch* s, uint32_t n_words_bitmap) {
+    uint32_t* w = reinterpret_cast<uint32_t*>(s);
+    const uint32_t n = static_cast<uint32_t>(offsetof(StaticScratch, layers) / 4);
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) w[i] = 0u;
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {      // block 0 covers the control block's words itself (grid of 1 below)
+        s->ctl.final_runs = P3_NONE;
+        s->ctl.lo_word = n_words_bitmap;
+    }
+}
+
+struct StaticTableArgs {
+    int64_t elems[P3_STATIC_TABLE_CHUNK];
+    int64_t offset[P3_STATIC_TABLE_CHUNK];
+    int32_t first[P3_STATIC_TABLE_CHUNK];
+    int32_t count[P3_STATIC_TABLE_CHUNK];
+    int64_t S;
+    int32_t base;         // index of the chunk's first layer
+    int32_t n;            // layers in this chunk
+};
+
+// The slice table (Sec. 4.2) written on the device: workgroup b describes layer base + b.
+__global__ void p3_static_table_kernel(StaticScratch* s, const StaticTableArgs a) {
+    const int b = blockIdx.x;
+    if (b >= a.n) return;
+    const int layer = a.base + b;
+    if (threadIdx.x == 0) {
+        P3LayerDev ld;
+        ld.first = a.first[b];
+        ld.count = a.count[b];
+        ld.elems = a.elems[b];
+        s->layers[layer] = ld;
+    }
+    for (int i = threadIdx.x; i < a.count[b]; i += blockDim.x) {
+        P3SliceDev sl;
+        sl.start = a.offset[b] + static_cast<int64_t>(i) * a.S;
+        const int64_t left = a.elems[b] - static_cast<int64_t>(i) * a.S;
+        sl.len = static_cast<int32_t>(left < a.S ? left : a.S);
+        sl.layer = layer;
+        sl.layer_slices = a.count[b];
+        sl.index_in_layer = i;
+        sl.layer_elems = a.elems[b];
+        s->slices[a.first[b] + i] = sl;
+    }
+}
+
+// What the caller gets back: slices claimed, how selector and workers ended, layers published.
+__global__ void p3_static_result_kernel(const StaticScratch* s, int32_t L, uint32_t iter_seq, int32_t* result) {
+    __shared__ int n_done;
+    if (threadIdx.x == 0) n_done = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int l = threadIdx.x; l < L; l += blockDim.x)
+        if (__hip_atomic_load(&s->done_flag[l], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == iter_seq) mine += 1;
+    atomicAdd(&n_done, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        result[0] = static_cast<int32_t>(s->hs.last_claimed);
+        result[1] = static_cast<int32_t>(s->hs.last_status);
+        result[2] = static_cast<int32_t>(s->hs.worker_status);
+        result[3] = n_done;
+    }
+}
+
+}  // namespace
+
+extern "C" int p3_drain_static(const p3_plan_t* p, int32_t W, const void* const* grads, int32_t grad_dtype,
+                               float* weights, float* momentum, float lr, float mu, float rescale, float wd,
+                               const int32_t* ready_layers, int32_t n_ready, int32_t* order_out,
+                               int32_t* result_out, void* hip_stream) {
+    if (!p || !grads || !weights || !momentum || !order_out || !result_out) return P3_ERR_ARG;
+    if (n_ready < 0 || (n_ready > 0 && !ready_layers)) return P3_ERR_ARG;
+    if (grad_dtype != P3_GRAD_FP32 && grad_dtype != P3_GRAD_BF16) return P3_ERR_ARG;
+    if (W < 1 || W > P3_MAX_WORKERS) return P3_ERR_RANGE;
+    if (p->n_shards != 1) return P3_ERR_ARG;
+    if (p->L > P3_STATIC_MAX_LAYERS || p->K > P3_STATIC_MAX_SLICES) return P3_ERR_RANGE;   // beyond the static array
+    auto misaligned = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) != 0; };
+    if (misaligned(weights) || misaligned(momentum)) return P3_ERR_ARG;
+    for (int32_t k = 0; k < W; ++k)
+        if (!grads[k] || misaligned(grads[k])) return P3_ERR_ARG;
+    uint8_t seen[P3_STATIC_MAX_LAYERS] = {0};
+    for (int32_t i = 0; i < n_ready; ++i) {
+        const int32_t l = ready_layers[i];
+        if (l < 0 || l >= p->L) return P3_ERR_RANGE;
+        if (seen[l]) return P3_ERR_ALREADY;
+        seen[l] = 1;
+    }
+    const int32_t tile = P3_BLOCK * 4;
+    const int64_t tiles = total_tiles(p, tile);
+    if (tiles > INT32_MAX - 65536) return P3_ERR_RANGE;
+
+    StaticDevice* d = nullptr;
+    if (int rc = static_state(&d)) return rc;
+    StaticScratch* s = d->ptr;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int32_t n_words = (p->K + 63) / 64;
+
+    hipLaunchKernelGGL(p3_static_clear_kernel, dim3(1), dim3(1024), 0, st, s, static_cast<uint32_t>(n_words));
+    if (HIPC(hipGetLastError()) != hipSuccess) return P3_ERR_DEVICE;
+    for (int32_t base = 0; base < p->L; base += P3_STATIC_TABLE_CHUNK) {
+        StaticTableArgs t;
+        std::memset(&t, 0, sizeof t);
+        t.S = p->S;
+        t.base = base;
+        t.n = p->L - base < P3_STATIC_TABLE_CHUNK ? p->L - base : P3_STATIC_TABLE_CHUNK;
+        for (int32_t i = 0; i < t.n; ++i) {
+            t.elems[i] = p->layers[base + i].elems;
+            t.offset[i] = p->offset[base + i];
+            t.first[i] = p->layers[base + i].first;
+            t.count[i] = p->layers[base + i].count;
+        }
+        hipLaunchKernelGGL(p3_static_table_kernel, dim3(static_cast<unsigned>(t.n)), dim3(256), 0, st, s, t);
+        if (HIPC(hipGetLastError()) != hipSuccess) return P3_ERR_DEVICE;
+    }
+    if (n_ready > 0) {
+        P3DrainArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.slices = s->slices;
+        a.layers = s->layers;
+        a.release = s->release;
+        a.bitmap = s->bitmap;
+        a.layer_state = s->layer_state;
+        a.runq = s->runq;
+        a.order = order_out;
+        a.epoch = s->epoch;
+        a.layer_done = s->layer_done;
+        a.layer_req = s->layer_req;
+        a.fifo = s->fifo;
+        a.t_seen_dev = s->t_seen_dev;
+        a.ctl = &s->ctl;
+        a.hs = &s->hs;
+        a.mark_log = s->mark_log;
+        a.done_flag = s->done_flag;
+        a.t_seen = s->t_seen;
+        a.t_done = s->t_done;
+        a.w = weights;
+        a.m = momentum;
+        a.arena_elems = p->arena;
+        a.K = p->K;
+        a.L = p->L;
+        a.n_words = n_words;
+        a.mark_cap = 64;
+        a.run_cap = P3_STATIC_MAX_SLICES;
+        a.tile_elems = tile;
+        a.tiles_per_full_slice = tiles_of(p->S < INT32_MAX ? p->S : INT32_MAX, tile);
+        a.epoch_base = 0;
+        a.epoch_limit = static_cast<uint64_t>(n_ready);
+        a.watchdog_ticks = 10000ull * static_cast<uint64_t>(d->clock_khz);
+        unsigned grid = static_cast<unsigned>(d->num_cu);
+        if (tiles < static_cast<int64_t>(grid)) grid = tiles < 2 ? 2u : static_cast<unsigned>(tiles);
+        a.lookahead = 2u * grid;
+        a.iter_seq = 1u;
+        a.mode = P3_MODE_SNAPSHOT;
+        a.policy = P3_POLICY_PRIORITY;
+        a.iter_begin = 1;
+        a.n_blocks = grid;
+        a.W = W;
+        a.lr = lr;
+        a.mu = mu;
+        a.rescale = rescale;
+        a.wd = wd;
+        a.early_number = tiles < P3_EARLY_BELOW_TILES_PER_WG * static_cast<int64_t>(grid) ? 1 : 0;
+        a.n_inline = n_ready;
+        for (int32_t i = 0; i < n_ready; ++i) a.inline_marks[i] = ready_layers[i];
+        P3GradPtrs gp;
+        std::memset(&gp, 0, sizeof gp);
+        for (int32_t k = 0; k < W; ++k) gp.p[k] = grads[k];
+        if (HIPC(static_cast<hipError_t>(p3_launch_drain(&a, &gp, grad_dtype, 1, grid, st))) != hipSuccess)
+            return P3_ERR_DEVICE;
+    }
+    hipLaunchKernelGGL(p3_static_result_kernel, dim3(1), dim3(256), 0, st, s, p->L, 1u, result_out);
+    if (HIPC(hipGetLastError()) != hipSuccess) return P3_ERR_DEVICE;
+    return P3_OK;
+}
