@@ -8,8 +8,11 @@ already resident in HBM.  Workload: the VGG-19-shaped parameter set, W = 8 fp32
 gradient copies, slices of 50,000 parameters (paper Sec. 5.7), SGD momentum.
 
 Prints ONE JSON line: aggregated-gradient GB/s (whole job), the HBM roofline of
-the drain kernel measured with HIP events on the drain's stream, the layer-0
-update latency in live mode, and the CPU oracle timed on the host beside it.
+the drain kernel measured with HIP events on the drain's stream (average, median
+and minimum over the timed launches), per-iteration median and minimum from event
+pairs, the layer-0 update latency in live mode, and the CPU oracle timed on the
+host beside it.  The arenas lie where the library's own hint puts them
+(p3_suggest_arena_stride); a probe of the naive placement is reported beside it.
 """
 import argparse
 import json
@@ -139,11 +142,11 @@ def parse():
     ap.add_argument("--tile-elems", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--persistent", type=int, default=-1, help="1: one fused launch per drain, 0: selector + workers")
-    ap.add_argument("--stagger", type=int, default=0,
-                    help="carve all arenas from one buffer, arena i shifted by i*STAGGER bytes (multiple of 256); "
-                         "-1: separate allocations")
-    ap.add_argument("--placement-trials", type=int, default=8,
-                    help="arena placements tried before the timed region (1: the first allocation is used as it is)")
+    ap.add_argument("--placement", default="suggested", choices=["suggested", "packed", "separate", "search", "best"],
+                    help="where the arenas lie: at the distance p3_suggest_arena_stride gives (default), back to back, "
+                         "in separate allocations; 'search' also probes other distances and reports them (the timed "
+                         "run stays on the suggested one), 'best' times the fastest of them")
+    ap.add_argument("--placement-trials", type=int, default=6, help="distances probed by --placement search/best")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy 3 times (reference for HBM byte counters)")
     ap.add_argument("--shards", type=int, default=1,
@@ -196,42 +199,64 @@ def main():
     arena = b.p3_arena_elems(plan)
 
     grads, w0, m0 = sy.make_inputs(cfg, threads=min(16, os.cpu_count() or 1))
+    dtype_code = b.P3_GRAD_BF16 if bf16 else b.P3_GRAD_FP32
+    per = (arena * 4 + (1 << 21) - 1) // (1 << 21) * (1 << 21)              # an arena rounded up to 2 MiB
+    held = []                                                                 # device allocations alive
 
-    pool, pool_at = None, 0
-    if args.stagger >= 0:
-        assert args.stagger % 256 == 0
-        per = (arena * 4 + (1 << 21) - 1) // (1 << 21) * (1 << 21)          # 2 MiB slots
-        pool = torch.empty((W + 2) * (per + args.stagger) + (1 << 21), dtype=torch.uint8, device="cuda")
+    def release(pl):
+        held[:] = [x for x in held if x is not pl["pool"]]
+        pl["pool"], pl["views"] = None, None
 
-    def dev(a):
-        nonlocal pool_at
-        x = sy.flat_to_arena(a, sizes, offs, arena)
-        t = torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x)
-        if pool is None:
-            return t.cuda()
-        nbytes = t.numel() * t.element_size()
-        view = pool[pool_at:pool_at + nbytes].view(t.dtype)
-        view.copy_(t)
-        pool_at += per + args.stagger
-        return view
+    def place(slot, src=None):
+        """All W + 2 arenas in one fresh allocation, `slot` bytes apart (slot < 0: separate allocations).
+        Data comes from the host (src None) or from another placement's views (copied on the device)."""
+        pool = None if slot < 0 else torch.empty((W + 2) * slot + (1 << 21), dtype=torch.uint8, device="cuda")
+        views = []
+        for i in range(W + 2):
+            if src is None:
+                a = grads[i] if i < W else (w0 if i == W else m0)
+                x = sy.flat_to_arena(a, sizes, offs, arena)
+                t = torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x)
+            else:
+                t = src[i]
+            if pool is None:
+                views.append(t.cuda() if src is None else t.clone())
+            else:
+                nbytes = t.numel() * t.element_size()
+                v = pool[i * slot:i * slot + nbytes].view(t.dtype)
+                v.copy_(t)
+                views.append(v)
+        torch.cuda.synchronize()
+        if pool is not None:
+            held.append(pool)
+        return {"slot": slot, "pool": pool, "views": views}
 
-    g = [dev(x) for x in grads]
-    w, m = dev(w0), dev(m0)
+    def bind(pl):
+        v = pl["views"]
+        b.p3_bind(plan, [t.data_ptr() for t in v[:W]], dtype_code, v[W].data_ptr(), v[W + 1].data_ptr())
+
     stream = torch.cuda.Stream()
-    torch.cuda.synchronize()
     if args.tile_elems or args.wgs_per_cu:
         b.p3_set_tuning(plan, args.tile_elems, args.wgs_per_cu, 0, 0)
-    b.p3_bind(plan, [t.data_ptr() for t in g], b.P3_GRAD_BF16 if bf16 else b.P3_GRAD_FP32,
-              w.data_ptr(), m.data_ptr())
-    b.p3_set_hyper(plan, cfg["lr"], cfg["mu"])
-    if args.persistent >= 0:
-        b.p3_set_launch(plan, args.persistent)
     order = list(range(L - 1, -1, -1))
 
     def step():
         b.p3_begin_iter(plan)
         b.p3_mark_ready_many(plan, order)
         b.p3_drain(plan, stream.cuda_stream)
+
+    def probe(pl, n=8):
+        """Average kernel time of n drains on a placement (after two untimed ones)."""
+        bind(pl)
+        for _ in range(2):
+            step()
+        b.p3_sync(plan)
+        b.p3_profile_enable(plan, True)
+        for _ in range(n):
+            step()
+        ms, cnt = b.p3_profile_read(plan)
+        b.p3_profile_enable(plan, False)
+        return ms / max(cnt, 1)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -241,68 +266,73 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # Where the arenas lie physically moves the rate by up to 3.5 % from one allocation to the next (same
-    # sizes, same process), so, like a server would at start-up, the arenas are tried at a few spacings
-    # inside a fresh allocation each, a short probe is timed, and the fastest placement is kept.  All of
-    # this happens before the timed region; the trials are reported.
-    placement, held = None, []
-    if pool is not None and args.placement_trials > 1 and arena * 4 >= (64 << 20):     # pointless for tiny models
-        def probe():
-            for _ in range(2):
-                step()
-            b.p3_sync(plan)
-            b.p3_profile_enable(plan, True)
-            for _ in range(8):
-                step()
-            ms, n = b.p3_profile_read(plan)
-            b.p3_profile_enable(plan, False)
-            return ms / max(n, 1)
-
-        slot0 = per + args.stagger
-        gib = 1 << 30
-        unit = (arena * 4 + (256 << 20) - 1) // (256 << 20) * (256 << 20)       # the arena rounded up to 256 MiB
-        slots = [slot0, (arena * 4 + gib - 1) // gib * gib, unit, unit + (256 << 20), 2 * gib, 2 * gib + (256 << 20),
-                 2 * gib + (512 << 20), unit + (512 << 20)]
-        slots = [x for i, x in enumerate(slots) if x >= arena * 4 and x not in slots[:i]][:args.placement_trials]
-        held = [pool]
-        best = {"slot": slot0, "pool": pool, "views": g + [w, m], "ms": probe()}
-        trials = [{"slot_MiB": round(slot0 / 2 ** 20, 1), "probe_kernel_ms": round(best["ms"], 4)}]
-        for slot in slots[1:]:
-            if torch.cuda.mem_get_info()[0] < (W + 2) * slot + (4 << 30):
-                continue                                   # not enough free device memory to try this one as well
-            try:
-                cand_pool = torch.empty((W + 2) * slot + (1 << 21), dtype=torch.uint8, device="cuda")
-            except RuntimeError:                           # out of device memory after all: go on with what there is
-                continue
-            cand = []
-            for i, v in enumerate(best["views"]):
-                nbytes = v.numel() * v.element_size()
-                nv = cand_pool[i * slot:i * slot + nbytes].view(v.dtype)
-                nv.copy_(v)
-                cand.append(nv)
+    # Where the arenas lie moves the rate by several per cent.  The timed run uses the placement the library
+    # itself suggests (p3_suggest_arena_stride: one allocation, a fixed distance between the arenas), with no
+    # search.  Beside it the line reports a short probe of the naive placement (arenas back to back), and with
+    # --placement search a few other spacings are probed as well (one candidate at a time: never more than
+    # two placements are alive), without changing what is timed unless --placement best is given.
+    suggested = b.p3_suggest_arena_stride(plan, dtype_code)
+    first_slot = {"suggested": suggested, "packed": per, "separate": -1}.get(args.placement, suggested)
+    if args.placement in ("search", "best"):
+        first_slot = suggested
+    chosen = place(first_slot)
+    bind(chosen)
+    b.p3_set_hyper(plan, cfg["lr"], cfg["mu"])
+    if args.persistent >= 0:
+        b.p3_set_launch(plan, args.persistent)
+    placement = {"mode": args.placement, "suggested_slot_MiB": round(suggested / 2 ** 20, 1),
+                 "timed_slot_MiB": round(first_slot / 2 ** 20, 1) if first_slot > 0 else "separate allocations"}
+    big = arena * 4 >= (64 << 20)                       # a probe is pointless for tiny models
+    if big and args.placement != "packed" and torch.cuda.mem_get_info()[0] > (W + 2) * per + (8 << 30):
+        timed_probe = probe(chosen)
+        packed = place(per, chosen["views"])
+        packed_ms = probe(packed)
+        placement["probe_kernel_ms"] = {"timed_placement": round(timed_probe, 4), "packed": round(packed_ms, 4)}
+        placement["packed_frac"] = round((W * bg + 16) * N / (packed_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+        trials = []
+        if args.placement in ("search", "best"):
+            gib = 1 << 30
+            unit = (arena * 4 + (256 << 20) - 1) // (256 << 20) * (256 << 20)
+            slots = [gib * ((arena * 4 + gib - 1) // gib), unit, unit + (256 << 20), 2 * gib, 2 * gib + (256 << 20),
+                     2 * gib + (512 << 20), unit + (512 << 20), 3 * gib]
+            slots = [x for i, x in enumerate(slots) if x >= arena * 4 and x not in slots[:i] and x != suggested
+                     and x != per][:args.placement_trials]
+            best, best_ms = chosen, timed_probe
+            release(packed)                                # its probe is on record
+            for slot in slots:
+                if torch.cuda.mem_get_info()[0] < (W + 2) * slot + (4 << 30):
+                    continue
+                cand = place(slot, best["views"])
+                ms = probe(cand)
+                trials.append({"slot_MiB": round(slot / 2 ** 20, 1), "probe_kernel_ms": round(ms, 4)})
+                loser = cand if ms >= best_ms else best
+                if ms < best_ms:
+                    best, best_ms = cand, ms
+                release(loser)
+            placement["trials"] = trials
+            placement["best_slot_MiB"] = round(best["slot"] / 2 ** 20, 1)
+            if args.placement == "best":
+                chosen = best
+                placement["timed_slot_MiB"] = placement["best_slot_MiB"]
+            elif best is not chosen:
+                chosen = place(suggested, best["views"])
+                release(best)
+            # released device memory is cleared by the driver in the background, which was measured to slow
+            # the drains that follow by 1 % for a few seconds: wait that out before the timed region
             torch.cuda.synchronize()
-            b.p3_bind(plan, [t.data_ptr() for t in cand[:W]], b.P3_GRAD_BF16 if bf16 else b.P3_GRAD_FP32,
-                      cand[W].data_ptr(), cand[W + 1].data_ptr())
-            ms = probe()
-            trials.append({"slot_MiB": round(slot / 2 ** 20, 1), "probe_kernel_ms": round(ms, 4)})
-            if ms < best["ms"]:
-                best = {"slot": slot, "pool": cand_pool, "views": cand, "ms": ms}
-            # nothing is freed before the timed region: the driver clears released device memory in the
-            # background, and that traffic was measured to slow the drains that follow by 1 % for seconds
-            held.append(cand_pool)
-        pool = best["pool"]
-        g, w, m = best["views"][:W], best["views"][W], best["views"][W + 1]
-        b.p3_bind(plan, [t.data_ptr() for t in g], b.P3_GRAD_BF16 if bf16 else b.P3_GRAD_FP32,
-                  w.data_ptr(), m.data_ptr())
-        placement = {"trials": trials, "chosen_slot_MiB": round(best["slot"] / 2 ** 20, 1),
-                     "held_GiB": round(sum(x.numel() for x in held) / 2 ** 30, 1)}
+            time.sleep(4.0)
+        bind(chosen)
+        placement["held_GiB"] = round(sum(x.numel() for x in held) / 2 ** 30, 1)
+    g, w, m = chosen["views"][:W], chosen["views"][W], chosen["views"][W + 1]
 
     for _ in range(args.warmup):
         step()
     b.p3_sync(plan)
     torch.cuda.synchronize()
 
-    b.p3_profile_enable(plan, True)          # HIP events around every drain kernel, on its stream
+    # Timed region: K iterations back to back (whole-job rate); the drain kernel of each is bracketed by the
+    # library's own HIP event pair on the drain's stream (roofline: average, median, minimum).
+    b.p3_profile_enable(plan, True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -310,11 +340,23 @@ def main():
     b.p3_sync(plan)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kern_ms, launches = b.p3_profile_read(plan)
+    kern_ms, launches, kern_each = b.p3_profile_read(plan, each=args.steps)
     sel_first_ns, sel_done_ns = b.p3_selector_timeline_ns(plan)
     b.p3_profile_enable(plan, False)
     claimed = b.p3_query_order(plan)
     assert claimed.shape[0] == K and (claimed == owned).all(), "drain did not claim every slice in order"
+    # A second pass of K iterations, each between its own pair of HIP events on the drain's stream: median and
+    # minimum per iteration (the events themselves cost about 10 us per iteration, so this pass is not the
+    # one the whole-job rate is taken from).
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    for i in range(args.steps):
+        ev0[i].record(stream)
+        step()
+        ev1[i].record(stream)
+    b.p3_sync(plan)
+    torch.cuda.synchronize()
+    iter_each = np.array([a.elapsed_time(c) for a, c in zip(ev0, ev1)])
 
     ms_per_step = elapsed / args.steps * 1e3
     agg_gbps = W * N * bg / (elapsed / args.steps) / 1e9
@@ -362,6 +404,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_iteration_events": {"median": round(float(np.median(iter_each)), 4), "min": round(float(iter_each.min()), 4),
+                                "note": "second pass of the same K iterations, one HIP event pair per iteration"},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -384,7 +428,9 @@ def main():
         "selector_us": {"first_publication": round(sel_first_ns / 1e3, 2), "finished": round(sel_done_ns / 1e3, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args, S),
-                     "kernel": "p3_drain_kernel", "kernel_avg_ms": round(kern_avg_ms, 4), "launches": launches,
+                     "kernel": "p3_drain_kernel", "kernel_avg_ms": round(kern_avg_ms, 4),
+                     "kernel_median_ms": round(float(np.median(kern_each)), 4),
+                     "kernel_min_ms": round(float(kern_each.min()), 4), "launches": launches,
                      "bytes_per_launch": bytes_per_launch},
     }
 

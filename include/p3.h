@@ -7,9 +7,9 @@
  * Sec. 4.2), a slice inherits the priority of its layer -- earlier in forward
  * order = more urgent (Sec. 4) -- and ready slices are aggregated over the W
  * workers' gradient copies and SGD-updated most-urgent-first (Sec. 4.2), with
- * the updated parameters published as soon as they are written (Sec. 4.2,
- * "immediately broadcasts").  The W workers are W gradient arenas resident in
- * this GPU's memory.
+ * the updated parameters published as soon as they are written (Sec. 4.2: the
+ * server sends a slice out right after updating it).  The W workers are W
+ * gradient arenas resident in this GPU's memory.
  *
  * Conventions
  *  - Every function returns a status (0 = P3_OK, negative = error) unless noted;
@@ -115,21 +115,26 @@ int p3_slice_info(const p3_plan_t* plan, int32_t g, int32_t* layer, int64_t* off
  * Allocates the library's own control buffers on the current HIP device
  * (slice table, ready bitmap, work queue, order log; a few bytes per slice).
  * May be called again to re-bind other buffers when no drain is in flight.
- * Placement matters to the rate: arenas carved from one device allocation were
- * measured 2 to 5 % faster than W+2 separate allocations, and the distance
- * between the arenas inside the allocation moves the rate by another 7 % between
- * the best and the worst value tried (on MI355X 2.25 and 2.5 GiB were best, the
- * arenas back to back 1.5 % slower); a caller who cares tries a few at start-up.
+ * Placement matters to the rate (several per cent): see p3_suggest_arena_stride.
  * Errors: ARG, RANGE (W), STATE (drain in flight), NOMEM, DEVICE. */
 int p3_bind(p3_plan_t* plan, int32_t W, const void* const* grads, int32_t grad_dtype,
             float* weights, float* momentum);
+
+/* Where to put the arenas.  Returns the distance in bytes to leave between the
+ * bases of the W + 2 arenas (gradient copies, weights, momentum) when they are
+ * carved from ONE device allocation -- the placement that was measured fastest
+ * on MI355X: 2^29 gradient elements (2 GiB for fp32 copies, 1 GiB for bf16), or
+ * the next multiple of that for longer arenas; arenas back to back were 2 to 5 %
+ * slower, separate allocations slower still.  A hint only: any 16-byte aligned
+ * placement is accepted by p3_bind.  Host-only.  Negative: ARG. */
+int64_t p3_suggest_arena_stride(const p3_plan_t* plan, int32_t grad_dtype);
 
 /* SGD hyper-parameters, taken by the next drain.  Per element, in fp32 with one
  * rounding per operation and no fused multiply-add:
  *   s = g_0 + g_1 + ... + g_{W-1}   (left to right; bf16 widened exactly)
  *   if rescale != 1: s = rescale*s ;  if wd != 0: s = s + wd*w
  *   m' = mu*m - lr*s ;  w' = w + m'
- * ("aggregates the gradients and updates the parameters", Sec. 2, Sec. 4.1.)
+ * (The server's work on a key once all workers have pushed it: Sec. 2, Sec. 4.1.)
  * Defaults: lr 0.1, mu 0.9, rescale 1, wd 0. */
 int p3_set_hyper(p3_plan_t* plan, float lr, float mu, float rescale, float wd);
 
@@ -185,7 +190,7 @@ int p3_set_tuning(p3_plan_t* plan, int32_t tile_elems, int32_t wgs_per_cu,
  * workgroup on every compute unit and holds them until the iteration is
  * applied; a LIVE drain, or one that waits for marks made on a producer stream
  * (p3_mark_ready_on_stream), would then keep the producer's own kernels (the
- * backward pass of Section 3.2 and 4.3 that the transfer is meant to overlap)
+ * backward pass that the transfer is meant to overlap: Sec. 3, Sec. 4.2)
  * from being scheduled until its wait runs out.  With n_cus > 0 the launch has
  * that many fewer workgroups, so the producer always finds free units; the
  * aggregation rate drops in proportion.  0 (default) uses the whole device; at
@@ -330,9 +335,11 @@ int p3_selector_timeline_ns(p3_plan_t* plan, int64_t* first_publish_ns, int64_t*
 
 /* Optional HIP-event bracketing of every drain kernel, on the drain's stream.
  * p3_profile_read: accumulated kernel milliseconds and launch count since the
- * last p3_profile_enable(plan, 1); waits for issued drains. */
+ * last p3_profile_enable(plan, 1), and, into the host array each_ms[cap] (may be
+ * NULL with cap 0), the kernel milliseconds of the first min(cap, launches)
+ * launches one by one; waits for issued drains.  Errors: ARG, STATE, NOMEM. */
 int p3_profile_enable(p3_plan_t* plan, int32_t on);
-int p3_profile_read(p3_plan_t* plan, double* total_ms, int32_t* launches);
+int p3_profile_read(p3_plan_t* plan, double* total_ms, int32_t* launches, float* each_ms, int32_t cap);
 
 /* ---- one iteration that allocates nothing ----
  * For callers that cannot allocate: code under HIP graph capture, tight serving

@@ -45,6 +45,7 @@ SIGNATURES = {
     "p3_layer_first_slice": (_i32, [_vp, _i32]),
     "p3_layer_num_slices": (_i32, [_vp, _i32]),
     "p3_slice_info": (C.c_int, [_vp, _i32, _P(_i32), _P(_i64), _P(_i32)]),
+    "p3_suggest_arena_stride": (_i64, [_vp, _i32]),
     "p3_bind": (C.c_int, [_vp, _i32, _P(_vp), _i32, _vp, _vp]),
     "p3_set_hyper": (C.c_int, [_vp, _f32, _f32, _f32, _f32]),
     "p3_set_mode": (C.c_int, [_vp, _i32, _P(_i64)]),
@@ -70,7 +71,7 @@ SIGNATURES = {
     "p3_drain_status": (C.c_int, [_vp, _P(_i32), _P(_i32), _P(_i32), _P(_i32)]),
     "p3_selector_timeline_ns": (C.c_int, [_vp, _P(_i64), _P(_i64)]),
     "p3_profile_enable": (C.c_int, [_vp, _i32]),
-    "p3_profile_read": (C.c_int, [_vp, _P(C.c_double), _P(_i32)]),
+    "p3_profile_read": (C.c_int, [_vp, _P(C.c_double), _P(_i32), _P(C.c_float), _i32]),
     "p3_drain_static": (C.c_int, [_vp, _i32, _P(_vp), _i32, _vp, _vp, _f32, _f32, _f32, _f32, _P(_i32), _i32, _vp, _vp,
                                   _vp]),
     "p3_last_hip_error": (C.c_int, [_P(C.c_int)]),
@@ -215,6 +216,13 @@ def p3_slice_info(plan, g):
     layer, off, ln = _i32(), _i64(), _i32()
     _check(load().p3_slice_info(_h(plan), int(g), C.byref(layer), C.byref(off), C.byref(ln)), "p3_slice_info")
     return layer.value, off.value, ln.value
+
+
+def p3_suggest_arena_stride(plan, grad_dtype):
+    r = load().p3_suggest_arena_stride(_h(plan), int(grad_dtype))
+    if r < 0:
+        _check(int(r), "p3_suggest_arena_stride")
+    return int(r)
 
 
 def p3_bind(plan, grad_ptrs, grad_dtype, weights_ptr, momentum_ptr):
@@ -366,7 +374,13 @@ def p3_profile_enable(plan, on=True):
     _check(load().p3_profile_enable(_h(plan), 1 if on else 0), "p3_profile_enable")
 
 
-def p3_profile_read(plan):
+def p3_profile_read(plan, each=0):
+    """(total ms, launches), and with each=n also a float32 array of the first n launches' kernel ms."""
     ms, n = C.c_double(), _i32()
-    _check(load().p3_profile_read(_h(plan), C.byref(ms), C.byref(n)), "p3_profile_read")
-    return ms.value, n.value
+    if not each:
+        _check(load().p3_profile_read(_h(plan), C.byref(ms), C.byref(n), None, 0), "p3_profile_read")
+        return ms.value, n.value
+    arr = np.zeros(int(each), dtype=np.float32)
+    _check(load().p3_profile_read(_h(plan), C.byref(ms), C.byref(n), arr.ctypes.data_as(_P(C.c_float)), int(each)),
+           "p3_profile_read")
+    return ms.value, n.value, arr[:min(int(each), n.value)].copy()

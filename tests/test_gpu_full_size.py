@@ -18,19 +18,26 @@ from p3_case import DeviceCase, PAD_W, assert_same_bits, to_device
 pytestmark = pytest.mark.gpu
 
 
-def test_vgg19_fp32_w8_full_size_two_iterations():
+def test_vgg19_fp32_w8_full_size_ten_iterations():
+    """The configuration the bandwidth target is quoted on, for the ten iterations it names: momentum
+    accumulated over ten updates of all 143,667,240 parameters, every bit against the oracle."""
     cfg = sy.config("vgg19")
     grads, w0, m0 = sy.make_inputs(cfg)
     case = DeviceCase(cfg["layers"], cfg["slice_elems"], grads, w0, m0)
     b.p3_set_hyper(case.plan, cfg["lr"], cfg["mu"])
     rw, rm = w0.copy(), m0.copy()
-    for _ in range(2):
-        case.iterate()
+    for it in range(cfg["iters"]):
+        case.iterate(many=True)
         oracle.sgd_whole(grads, rw, rm, cfg["lr"], cfg["mu"])
+        if it in (0, 4):                              # also part of the way, so that a late error is not the only check
+            case.sync()
+            assert (case.order() == np.arange(case.K)).all()
+            w, m = case.fetch()
+            assert_same_bits(w, m, rw, rm, f"vgg19 fp32 W=8 after iteration {it + 1}")
     case.sync()
     assert (case.order() == np.arange(case.K)).all()
     w, m = case.fetch()
-    assert_same_bits(w, m, rw, rm, "vgg19 fp32 W=8")
+    assert_same_bits(w, m, rw, rm, "vgg19 fp32 W=8, ten iterations")
     # live mode on the same plan, marks arriving while the drain runs: same arithmetic, and the
     # order log is a permutation that replays against the epochs the selector observed
     b.p3_set_mode(case.plan, b.P3_MODE_LIVE)
@@ -101,7 +108,7 @@ def test_vgg19_bf16_w16_slice_sweep_ticked():
         gw = sy.arena_to_flat(w.cpu().numpy(), sizes, offsets)
         gm = sy.arena_to_flat(m.cpu().numpy(), sizes, offsets)
         assert_same_bits(gw, gm, rw, rm, f"vgg19 bf16 W=16 S={S}")
-        if S in (4096, 50000):
+        if True:
             # the same release pattern in real time: a live drain, the host marking the layers in reverse
             # order with pauses in proportion to the release ticks (a few hundred microseconds in all)
             import time

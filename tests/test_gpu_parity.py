@@ -298,6 +298,29 @@ def test_live_mode_replay_and_weights():
     check(case, rw, rm, "live")
 
 
+@pytest.mark.parametrize("name", ["mlp", "resnet50"])
+def test_live_drain_launched_after_every_mark_claims_in_priority_order(name):
+    """Every layer is marked before the live drain is launched, so the selector must have seen all L marks at
+    its first claim and the order is the identity: a selector that picks marks up late would still replay
+    against its own trace, but not pass this."""
+    cfg = sy.config(name)
+    grads, w0, m0 = sy.make_inputs(cfg)
+    case = DeviceCase(cfg["layers"], 4096, grads, w0, m0, watchdog_ms=4000)
+    b.p3_set_hyper(case.plan, cfg["lr"], cfg["mu"])
+    b.p3_set_mode(case.plan, b.P3_MODE_LIVE)
+    rw, rm = w0.copy(), m0.copy()
+    for marks in (list(range(case.L - 1, -1, -1)), list(range(case.L))):
+        b.p3_begin_iter(case.plan)
+        for l in marks:
+            b.p3_mark_ready(case.plan, l)
+        b.p3_drain(case.plan, case.stream.cuda_stream)
+        case.sync(8000)
+        assert (case.order() == np.arange(case.K)).all()
+        assert (b.p3_query_trace(case.plan) == case.L).all()
+        oracle.sgd_whole(grads, rw, rm, cfg["lr"], cfg["mu"])
+    check(case, rw, rm, f"{name}: live drain after all marks")
+
+
 def test_live_marks_from_another_host_thread():
     """The documented threading rule: one thread drives the iteration, another may
     mark layers while the live drain runs (here while the first thread already
