@@ -517,14 +517,20 @@ __device__ __attribute__((noinline)) void post_retire(FlushCtx a, unsigned long 
 // Every workgroup of a launch registers with its XCD before it does anything else
 // (workgroup 0 of a fused launch before it starts selecting), so the set of XCDs a
 // round has to hear from is fixed when the first store is made.
-__device__ __forceinline__ void enter_xcd(P3Ctl* ctl, int xcd, int lane) {
+// (The selecting workgroup does not wait here: its first act that others can see is a publication
+// of the queue, which sits behind an agent-scope release fence of this same wavefront, and that
+// fence waits for these two operations as for every other one -- one round trip less in front of
+// the first publication.)
+__device__ __forceinline__ void enter_xcd(P3Ctl* ctl, int xcd, int lane, bool wait) {
     uint32_t u = 0u, v = 0u;
     if (lane_is(lane, 0)) {
         u = __hip_atomic_exchange(&ctl->xcd[xcd].used, 1u, __ATOMIC_RELAXED, P3_AGENT);
         v = __hip_atomic_fetch_add(&ctl->xcd[xcd].live, 1u, __ATOMIC_RELAXED, P3_AGENT);
     }
-    (void)uni(u);
-    (void)uni(v);                                  // performed before this workgroup stores anything
+    if (wait) {
+        (void)uni(u);
+        (void)uni(v);                              // performed before this workgroup stores anything
+    }
 }
 
 // Leaving the worker loop.  While other workgroups of the XCD stay, any write-back they make
@@ -781,11 +787,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: whole wavefronts branch on it
     P3Ctl* ctl = a.ctl;
 
-    if (lane_is(tid, 0)) {
-        a.hs->phase = P3P_ENTER;
-        a.hs->t_sel_enter = wall_clock64();
-        a.hs->t_sel_first_pub = 0;
-    }
+    const uint64_t t_entry = wall_clock64();
     // Memory ordering.  A store's acknowledgement (what `s_waitcnt vmcnt(0)` waits for; a
     // workgroup-scope fence waits for nothing here) only says that the store has reached the L2
     // of the issuing XCD; other XCDs see it once that L2 has written it back, and only an
@@ -846,15 +848,14 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
     st.pub_runs = 0u;
     st.pub_tiles = 0u;
     st.status = P3D_OK;
-    const uint64_t t_start = wall_clock64();
+    const uint64_t t_start = t_entry;
     const uint32_t inline_first = st.marks_applied;   // first mark this drain folds
     const FlushCtx sel_fc = {a.ctl, a.layer_req, a.t_seen_dev, a.t_seen, a.t_done, a.done_flag, a.iter_seq, a.L};
     const int sel_xcd = xcd_of_this_wave();
     uint32_t rounds = 0u;
-    if (lane_is(tid, 0)) {
-        a.hs->phase = P3P_RESET;
-        lds.overflow = 0;
-    }
+    // (Nothing is stored over the host link before the first publication: the release fence in front of a
+    // publication waits for every store this wavefront has outstanding, and one to host memory takes longest.)
+    if (lane_is(tid, 0)) lds.overflow = 0;
 
     for (;;) {
         if (wave == 0) {
@@ -1133,6 +1134,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                     if (lane_is(lane, 0)) {
                         __hip_atomic_store(&ctl->published, st.pub_runs, __ATOMIC_RELAXED, P3_AGENT);
                         if (first) {
+                            a.hs->t_sel_enter = t_entry;
                             a.hs->t_sel_first_pub = wall_clock64();   // first growth
                             a.hs->phase = P3P_PUBLISHED;
                         }
@@ -1235,7 +1237,8 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                 st.pub_tiles += static_cast<uint32_t>(tb);
                 if (lane_is(lane, 0)) {
                     __hip_atomic_store(&ctl->published, st.pub_runs, __ATOMIC_RELAXED, P3_AGENT);
-                    if (first) {                       // (one store over the host link per launch, not per step)
+                    if (first) {                       // (stores over the host link once per launch, not per step)
+                        a.hs->t_sel_enter = t_entry;
                         a.hs->t_sel_first_pub = wall_clock64();   // first growth
                         a.hs->phase = P3P_PUBLISHED;
                     }
@@ -1267,6 +1270,10 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
         a.hs->last_status = st.status;
         a.hs->last_iter = a.iter_seq;
         __hip_atomic_store(&ctl->final_runs, st.pub_runs, __ATOMIC_RELAXED, P3_AGENT);
+        if (st.pub_runs == 0u) {        // nothing was ever published: the stamps of a first publication were not written
+            a.hs->t_sel_enter = t_entry;
+            a.hs->t_sel_first_pub = 0;
+        }
         a.hs->t_sel_final = wall_clock64();
         a.hs->phase = P3P_FINAL;
     }
@@ -1303,7 +1310,8 @@ struct Located {
     P3Run run;          // the run that holds the tile (found != 0)
     uint32_t r_next;    // runs below this index end at or before the tile
     uint32_t r_have;    // runs below this index have been copied to the LDS ring
-    int32_t found;      // 0: the queue is complete (or the wait was given up) and has no such tile
+    int32_t found;      // 0: the queue is complete (or the wait was given up) and has no such tile; 1: found;
+                        // 2: the queue has not grown that far yet and the caller did not allow a wait
 };
 
 // Find the run that holds tile k.  Tile numbers only grow, so the search never
@@ -1314,7 +1322,8 @@ struct Located {
 // loads: the selector wrote them through before raising `published`.
 template <bool WAIT>
 __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc, int xcd, P3Run* ring, uint32_t k,
-                                                        uint32_t r_next, uint32_t r_have, uint64_t t_enter, int lane) {
+                                                        uint32_t r_next, uint32_t r_have, uint64_t t_enter, int lane,
+                                                        bool may_wait) {
     Located out;
     out.run.start = 0;
     out.run.len = 0;
@@ -1341,7 +1350,16 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
             }
             r_next = r_have - r_next > 64u ? r_next + 64u : r_have;
         }
-        const uint32_t pub = uni(__hip_atomic_load(&a.ctl->published, __ATOMIC_RELAXED, P3_AGENT));
+        // what a waiting workgroup needs from memory -- the queue's length, whether it is final, its XCD's
+        // write-back line -- is asked for at once: one round trip per look, not three in a row
+        uint32_t pub_v = __hip_atomic_load(&a.ctl->published, __ATOMIC_RELAXED, P3_AGENT);
+        uint32_t fin_v = P3_NONE;
+        u32x4 fv_v = {0u, 0u, 0u, 0u};
+        if (WAIT) {
+            fin_v = __hip_atomic_load(&a.ctl->final_runs, __ATOMIC_RELAXED, P3_AGENT);
+            fv_v = load_flush_view(a.ctl, xcd);
+        }
+        const uint32_t pub = uni(pub_v);
         if (pub > r_have) {
             // r_next == r_have: everything in the ring is dead, the whole ring may be refilled
             const uint32_t upto = pub - r_have > P3_RUN_CACHE ? r_have + P3_RUN_CACHE : pub;
@@ -1377,8 +1395,12 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
             continue;
         }
         if (!WAIT) break;                              // the queue was complete before this launch
-        const uint32_t fin = uni(__hip_atomic_load(&a.ctl->final_runs, __ATOMIC_RELAXED, P3_AGENT));
+        const uint32_t fin = uni(fin_v);
         if (fin != P3_NONE && r_have >= fin) break;    // the queue is complete and has no such tile
+        if (!may_wait) {                               // the caller has something to settle before it waits
+            out.found = 2;
+            break;
+        }
         // bounded wait: the selector turns a host abort into `final_runs`, so the workers
         // only need the clock (no host-memory reads from hundreds of spinners)
         if (wall_clock64() - t_enter > a.watchdog_ticks) {
@@ -1386,9 +1408,9 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
             break;
         }
         // a waiting workgroup still answers for its XCD in the write-back rounds
-        const FlushView fv = view_of(load_flush_view(a.ctl, xcd));
+        const FlushView fv = view_of(fv_v);
         if (flush_due(fv, true)) serve_flush(fc, fv.req, xcd, lane);
-        __builtin_amdgcn_s_sleep(8);
+        __builtin_amdgcn_s_sleep(4);
     }
     out.r_next = r_next;
     out.r_have = r_have;
@@ -1441,10 +1463,36 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
     uint32_t r_next = 0u, r_have = 0u;
     int pend_layer = 0, pend_tiles = 0;   // finished tiles of one layer not yet added to its count
     uint32_t pend_cnt = 0u;               // their elements
+    // retire counts that have been added but whose result (did this addition complete the layer?) has not
+    // been looked at yet: A = a layer the workgroup has left, B = the layer of the tile just finished
+    unsigned long long po_old_a = 0ull, po_old_b = 0ull;      // vector registers: what the additions return
+    unsigned long long po_le_a = 1ull, po_le_b = 1ull;        // vector registers: elements of the layers (loaded with
+                                                              // the additions, so that nothing waits for them alone)
+    uint32_t po_cnt_a = 0u, po_cnt_b = 0u;                    // what was added (0: nothing outstanding)
+    int po_layer_a = 0, po_layer_b = 0;
+    // Look at the outstanding results; a count that completed its layer starts the layer's publication.
+    auto settle = [&]() {
+        if (po_cnt_a != 0u) {
+            const unsigned long long old = uni(po_old_a);
+            if (old + static_cast<unsigned long long>(po_cnt_a) == uni(po_le_a)) {
+                if (old == 0ull) complete_alone(fc, po_layer_a, lane);
+                else complete_layer(fc, po_layer_a, xcd, lane);
+            }
+            po_cnt_a = 0u;
+        }
+        if (po_cnt_b != 0u) {
+            const unsigned long long old = uni(po_old_b);
+            if (old + static_cast<unsigned long long>(po_cnt_b) == uni(po_le_b)) {
+                if (old == 0ull) complete_alone(fc, po_layer_b, lane);
+                else complete_layer(fc, po_layer_b, xcd, lane);
+            }
+            po_cnt_b = 0u;
+        }
+    };
 
     if (wave == 0) {
         const uint32_t k = uni(take_ticket(ctl, lane));
-        const Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, r_next, r_have, t_enter, lane);
+        const Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, r_next, r_have, t_enter, lane, true);
         r_next = uni(f.r_next);
         r_have = uni(f.r_have);
         P3TileDesc d0;
@@ -1492,70 +1540,111 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
         __syncthreads();                                      // everyone's stores are out: the tile may be retired
 
         if (wave == 0) {
-            // Finished tiles are counted against their layer P3_RETIRE_BATCH at a time (the count of a big
-            // layer is one word that every workgroup adds to: fewer, larger additions), and at once when
-            // the workgroup moves on to another layer or run.
-            uint32_t post_cnt = 0u;
-            int post_layer = layer;
+            // What the additions of the previous round returned has long arrived (a whole tile was streamed
+            // meanwhile): look at it now.
+            settle();
+            // Counting finished tiles against their layer.  In a long run (a layer of thousands of tiles,
+            // whose count is one word that every workgroup adds to) a workgroup adds P3_RETIRE_BATCH tiles
+            // at a time: fewer, larger additions.  In a short run every tile is added at once: a workgroup
+            // gets a tile or two of such a run, and a count left pending would cost a round trip of its own
+            // when the next number falls into another run.  Counts of a layer the workgroup has left (A)
+            // and of the layer of this tile (B) travel together.
+            uint32_t cnt_a = 0u, cnt_b = 0u;
+            int layer_a = layer;
             if (pend_tiles > 0 && pend_layer != layer) {
-                post_cnt = pend_cnt;
-                post_layer = pend_layer;
-                pend_cnt = static_cast<uint32_t>(n);
-                pend_tiles = 1;
-            } else {
-                pend_cnt += static_cast<uint32_t>(n);
-                pend_tiles += 1;
-                if (pend_tiles >= P3_RETIRE_BATCH) {
-                    post_cnt = pend_cnt;
-                    pend_cnt = 0u;
-                    pend_tiles = 0;
-                }
+                cnt_a = pend_cnt;
+                layer_a = pend_layer;
+                pend_cnt = 0u;
+                pend_tiles = 0;
             }
+            pend_cnt += static_cast<uint32_t>(n);
+            pend_tiles += 1;
             pend_layer = layer;
-            // one round trip: retire count and layer size (if a count is due), next tile number, write-back rounds
-            unsigned long long old_v = 0ull, le_v = 1ull;
-            uint32_t tk_v = 0u;
-            if (post_cnt != 0u) {
-                if (lane_is(lane, 0))
-                    old_v = __hip_atomic_fetch_add(&a.layer_done[post_layer], static_cast<unsigned long long>(post_cnt),
-                                                   __ATOMIC_RELAXED, P3_AGENT);
-                le_v = static_cast<unsigned long long>(a.layers[post_layer].elems);
+            const bool long_run = cur.tile_end - cur.tile0 >= P3_LONG_RUN_TILES_PER_WG * a.n_blocks;
+            if (!long_run || pend_tiles >= P3_RETIRE_BATCH) {
+                cnt_b = pend_cnt;
+                pend_cnt = 0u;
+                pend_tiles = 0;
             }
+            if (cnt_a != 0u) {
+                if (lane_is(lane, 0))
+                    po_old_a = __hip_atomic_fetch_add(&a.layer_done[layer_a], static_cast<unsigned long long>(cnt_a),
+                                                      __ATOMIC_RELAXED, P3_AGENT);
+                po_le_a = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.layers[layer_a].elems),
+                                            __ATOMIC_RELAXED, P3_AGENT);
+                po_cnt_a = cnt_a;
+                po_layer_a = layer_a;
+            }
+            if (cnt_b != 0u) {
+                if (lane_is(lane, 0))
+                    po_old_b = __hip_atomic_fetch_add(&a.layer_done[layer], static_cast<unsigned long long>(cnt_b),
+                                                      __ATOMIC_RELAXED, P3_AGENT);
+                po_le_b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.layers[layer].elems),
+                                            __ATOMIC_RELAXED, P3_AGENT);
+                po_cnt_b = cnt_b;
+                po_layer_b = layer;
+            }
+            // The next tile number.  Asked for now (late), its round trip is exposed and the additions above
+            // ride on it: their results are there when the number is, and are looked at right away.  Asked
+            // for before the wait for the stores (early), it is here already, and nothing in this section
+            // waits for memory: the results of the additions are looked at one round later -- except for
+            // layer 0, the layer the next forward pass needs first, which never waits a round.
+            uint32_t tk_v = tk_pre;
             u32x4 fv_v = fv_pre;
-            if (early) {
-                tk_v = tk_pre;
-            } else {
+            if (!early) {
                 if (lane_is(lane, 0)) tk_v = __hip_atomic_fetch_add(&ctl->ticket, 1u, __ATOMIC_RELAXED, P3_AGENT);
                 fv_v = load_flush_view(ctl, xcd);
             }
-            const unsigned long long old = uni(old_v), le = uni(le_v);
             const uint32_t k = uni(tk_v);
             const FlushView fv = view_of(fv_v);
-            if (post_cnt != 0u && old + static_cast<unsigned long long>(post_cnt) == le) {
-                if (old == 0ull) complete_alone(fc, post_layer, lane);
-                else complete_layer(fc, post_layer, xcd, lane);
-            } else if (flush_due(fv, false)) {
-                serve_flush(fc, fv.req, xcd, lane);
-            }
+            if (!early || (po_cnt_a != 0u && po_layer_a == 0) || (po_cnt_b != 0u && po_layer_b == 0)) settle();
+            if (flush_due(fv, false)) serve_flush(fc, fv.req, xcd, lane);
 
             bool found = true;
             if (k >= cur.tile_end) {                          // left the run (or there was none yet)
-                if (pend_tiles > 0) {                         // nothing stays uncounted while the workgroup may have to wait
+                if (pend_tiles > 0) {                         // (only at the end of a long run)
                     post_retire(fc, a.layer_done, a.layers, pend_layer, pend_cnt, xcd, lane);
                     pend_cnt = 0u;
                     pend_tiles = 0;
                 }
-                const Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, r_next, r_have, t_enter, lane);
-                r_next = uni(f.r_next);
-                r_have = uni(f.r_have);
-                found = uni(f.found) != 0;
+                // The usual case, here in line: the run is one of the next 64 of the LDS copy (tile numbers and
+                // runs both only grow, so it is the first whose end lies beyond the number).  Everything else --
+                // a longer search, a refill of the copy, a wait for the queue to grow -- is the out-of-line
+                // function's business (calling it costs about a microsecond of argument traffic alone).
+                P3Run hit_run = cur;
+                bool hit = false;
+                if (r_next < r_have) {
+                    const uint32_t r = r_next + static_cast<uint32_t>(lane);
+                    const bool in = r < r_have;
+                    uint32_t te = 0u;
+                    if (in) te = s_runs[r & (P3_RUN_CACHE - 1)].tile_end;
+                    const unsigned long long hits = __ballot(in && k < te);
+                    if (hits != 0ull) {
+                        const uint32_t rf = r_next + static_cast<uint32_t>(__builtin_ctzll(hits));
+                        hit_run = s_runs[rf & (P3_RUN_CACHE - 1)];          // every lane reads the same entry
+                        r_next = rf + 1u;
+                        hit = true;
+                    }
+                }
+                if (!hit) {
+                    Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, r_next, r_have, t_enter, lane, false);
+                    if (uni(f.found) == 2) {
+                        // the queue has to grow first: nothing stays unlooked-at while the workgroup waits
+                        settle();
+                        f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, uni(f.r_next), uni(f.r_have), t_enter, lane, true);
+                    }
+                    r_next = uni(f.r_next);
+                    r_have = uni(f.r_have);
+                    found = uni(f.found) == 1;
+                    hit_run = f.run;
+                }
                 if (found) {
-                    cur.start = static_cast<int64_t>(uni(static_cast<unsigned long long>(f.run.start)));
-                    cur.len = static_cast<int64_t>(uni(static_cast<unsigned long long>(f.run.len)));
-                    cur.grid_off = uni(f.run.grid_off);
-                    cur.layer = uni(f.run.layer);
-                    cur.tile0 = uni(f.run.tile0);
-                    cur.tile_end = uni(f.run.tile_end);
+                    cur.start = static_cast<int64_t>(uni(static_cast<unsigned long long>(hit_run.start)));
+                    cur.len = static_cast<int64_t>(uni(static_cast<unsigned long long>(hit_run.len)));
+                    cur.grid_off = uni(hit_run.grid_off);
+                    cur.layer = uni(hit_run.layer);
+                    cur.tile0 = uni(hit_run.tile0);
+                    cur.tile_end = uni(hit_run.tile_end);
                 }
             }
             P3TileDesc dn;
@@ -1568,7 +1657,10 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
         __syncthreads();                                      // the next descriptor is in LDS
     }
 
-    if (wave == 0) leave_loop(fc, xcd, lane);
+    if (wave == 0) {
+        settle();                                             // the additions of the last round
+        leave_loop(fc, xcd, lane);
+    }
 
     // Last workgroup out re-arms the per-launch words for the next drain.
     if (lane_is(tid, 0)) {
@@ -1598,7 +1690,7 @@ __global__ void __launch_bounds__(P3_BLOCK) p3_drain_kernel(const P3DrainArgs a,
     __shared__ SelectorLds lds;
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
-    if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x));
+    if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), blockIdx.x != 0);
     if (blockIdx.x == 0) run_selector(a, lds);
     run_worker<WT, BF16, WD, true>(a, gp, s_desc, s_runs);
 }
@@ -1614,7 +1706,7 @@ template <int WT, bool BF16, bool WD>
 __global__ void __launch_bounds__(P3_BLOCK) p3_work_kernel(const P3DrainArgs a, const P3GradPtrs gp) {
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
-    if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x));
+    if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), true);
     run_worker<WT, BF16, WD, false>(a, gp, s_desc, s_runs);
 }
 

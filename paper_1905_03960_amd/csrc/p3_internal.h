@@ -14,7 +14,8 @@
 #define P3_NONE 0xffffffffu     // "final queue length not known yet"
 #define P3_MAXW 64
 #define P3_MAX_XCD 16           // L2 caches (accelerator complex dies) a launch can be spread over
-#define P3_RETIRE_BATCH 4           // tiles of one layer a workgroup finishes before it adds them to the layer's count
+#define P3_RETIRE_BATCH 4           // tiles of one long run a workgroup finishes before it adds them to the layer's count
+#define P3_LONG_RUN_TILES_PER_WG 8u // a run is long when it gives every workgroup at least this many tiles
 #define P3_PUBLISHED 0x80000000u   // layer_req: the layer's done flag has been written
 #define P3_FLUSH_GAP_TICKS 5000u   // busy workgroups leave 50 us (100 MHz clock) between two write-backs of one L2
 #ifndef P3_EARLY_BELOW_TILES_PER_WG
@@ -102,7 +103,7 @@ struct P3HostShared {
 };
 
 // selector progress codes written to P3HostShared::phase
-enum { P3P_ENTER = 1, P3P_RESET = 2, P3P_PUBLISHED = 5, P3P_FINAL = 6 };
+enum { P3P_PUBLISHED = 5, P3P_FINAL = 6 };
 
 struct P3GradPtrs {
     const void* p[P3_MAXW];
