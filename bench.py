@@ -141,6 +141,7 @@ def parse():
     ap.add_argument("--slice-elems", type=int, default=0)
     ap.add_argument("--tile-elems", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--reserved-cus", type=int, default=0, help="compute units the drain leaves to other streams")
     ap.add_argument("--persistent", type=int, default=-1, help="1: one fused launch per drain, 0: selector + workers")
     ap.add_argument("--placement", default="suggested", choices=["suggested", "packed", "separate", "search", "best"],
                     help="where the arenas lie: at the distance p3_suggest_arena_stride gives (default), back to back, "
@@ -238,6 +239,8 @@ def main():
     stream = torch.cuda.Stream()
     if args.tile_elems or args.wgs_per_cu:
         b.p3_set_tuning(plan, args.tile_elems, args.wgs_per_cu, 0, 0)
+    if args.reserved_cus:
+        b.p3_set_reserved_cus(plan, args.reserved_cus)
     order = list(range(L - 1, -1, -1))
 
     def step():

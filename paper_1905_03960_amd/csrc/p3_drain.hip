@@ -251,6 +251,11 @@ __device__ __forceinline__ void do_quads_f32(const P3GradPtrs& gp, int W, const 
     }
 #pragma unroll
     for (int u = 0; u < NV; ++u) sgd_step(s[u], wv[u], mv[u], h);
+    // Every load of the step has returned (the arithmetic needed them all), and with them -- the counter
+    // is one for loads and stores -- every store this wavefront issued for earlier tiles has been
+    // acknowledged.  The worker loop relies on that; the wait is stated here so that it does not depend on
+    // how the compiler places its own.
+    wait_vm_done();
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         store_out(rm, (local + u * P3_BLOCK) * 16, mv[u]);
@@ -308,6 +313,7 @@ __device__ __forceinline__ void do_quad_bf16(const P3GradPtrs& gp, int W, const 
     pin(wv);
     pin(mv);
     sgd_step(s, wv, mv, h);
+    wait_vm_done();                      // (as in do_quads_f32: earlier tiles' stores are acknowledged by now)
     store_out(rm, local * 16, mv);
     store_out(rw, local * 16, wv);
 }
@@ -320,7 +326,7 @@ __device__ __forceinline__ void do_quad_bf16(const P3GradPtrs& gp, int W, const 
 // arithmetic: a branch there (even a uniform one) was measured to cost 12 % of
 // the stream's bandwidth.
 template <int WT, bool BF16, class H>
-__device__ __forceinline__ void process_tile(const P3GradPtrs& gp, int W, float* __restrict__ w,
+__device__ __forceinline__ int32_t process_tile(const P3GradPtrs& gp, int W, float* __restrict__ w,
                                              float* __restrict__ m, int64_t start, int32_t n,
                                              const H& h) {
     constexpr int VEC = 4;                           // fp32 and bf16 gradients alike: one quad per lane
@@ -350,6 +356,7 @@ __device__ __forceinline__ void process_tile(const P3GradPtrs& gp, int W, float*
     if (tid < head) update_one<BF16>(gp, W, w, m, start + tid, h);
     const int t2 = tid - 64;
     if (t2 >= 0 && t2 < tail) update_one<BF16>(gp, W, w, m, body + static_cast<int64_t>(nvec) * VEC + t2, h);
+    return nvec;                                     // lanes below this number loaded and stored a quad
 }
 
 // --------------------------------------------------- completion of a layer ----
@@ -488,8 +495,11 @@ __device__ __attribute__((noinline)) void complete_layer(FlushCtx a, int layer, 
 
 // This workgroup's one retire count was the whole layer (the count stood at zero before it): every
 // store of the layer came from this workgroup, so only this XCD's L2 can hold any of it -- it is
-// written back here and the layer published at once, without a round among the XCDs.  This is the
-// case of a first layer of a few thousand parameters, the one whose latency matters most.
+// written back here and the layer published at once, without a round among the XCDs.  Used for layer
+// 0 only, the case of a first layer of a few thousand parameters, whose latency matters most: every
+// write-back stalls its XCD for a microsecond or so, and a model with a hundred one-tile layers (the
+// normalisation vectors of a ResNet) that wrote back for each of them lost 6 % of its drain to that;
+// the other layers wait for a round like everybody else.
 __device__ __attribute__((noinline)) void complete_alone(FlushCtx a, int layer, int lane) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     if (lane_is(lane, 0)) {
@@ -497,20 +507,6 @@ __device__ __attribute__((noinline)) void complete_alone(FlushCtx a, int layer, 
         a.t_seen[layer] = __hip_atomic_load(&a.t_seen_dev[layer], __ATOMIC_RELAXED, P3_AGENT);
         a.t_done[layer] = wall_clock64();
         __hip_atomic_store(&a.done_flag[layer], a.iter_seq, __ATOMIC_RELEASE, P3_SYSTEM);
-    }
-}
-
-// Add `cnt` finished elements to the count of `layer` and wait for the result (the leader's slow path).
-__device__ __attribute__((noinline)) void post_retire(FlushCtx a, unsigned long long* layer_done, const P3LayerDev* layers,
-                                                      int layer, uint32_t cnt, int xcd, int lane) {
-    unsigned long long old_v = 0ull;
-    if (lane_is(lane, 0))
-        old_v = __hip_atomic_fetch_add(&layer_done[layer], static_cast<unsigned long long>(cnt), __ATOMIC_RELAXED, P3_AGENT);
-    const unsigned long long le = uni(static_cast<unsigned long long>(layers[layer].elems));
-    const unsigned long long old = uni(old_v);
-    if (old + static_cast<unsigned long long>(cnt) == le) {
-        if (old == 0ull) complete_alone(a, layer, lane);
-        else complete_layer(a, layer, xcd, lane);
     }
 }
 
@@ -1423,18 +1419,30 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
 // by an earlier launch on the stream, so a number beyond its end means "no more
 // work".
 //
-// A round: every wavefront streams its share of the tile and waits for its
-// stores' acknowledgements; barrier; the leader draws the next tile number;
-// barrier.  The number is drawn as late as possible and its round trip is left
-// exposed on purpose: tiles then start in the order of their addresses all over
-// the chip, and that ordering is worth more HBM bandwidth than the round trip
-// costs (drawing one round ahead was measured at -3 %, two rounds at -5 %; 240
-// of the 256 compute units already saturate the memory).  The same round trip
-// carries the finished tile's retire count and the size of its layer.  What it
-// must not be followed by is a second, dependent trip to the queue, and there is
-// none: the leader keeps the run it is working in in scalar registers and a copy
-// of the run table in LDS, so turning a tile number into addresses is arithmetic
-// (and, at a run boundary, a search of LDS).
+// A round: every wavefront streams its share of the tile; the leader (wavefront
+// 0) asks for the next tile number; barrier; the leader does the bookkeeping;
+// barrier.  Nothing in a round waits for memory on purpose:
+//  * the next tile number is asked for when the leader has issued its share of
+//    the tile, and is usually there when the other wavefronts reach the barrier;
+//  * a tile is counted against its layer ONE ROUND LATE.  Nobody waits for the
+//    acknowledgements of a tile's stores: a wavefront's first wait for a load of
+//    the next tile (`s_waitcnt vmcnt(n)`, n small; the counter covers loads and
+//    stores alike, in issue order) cannot end before the stores of the tile
+//    before have been acknowledged, so behind the barrier of round r every store
+//    of tile r-1 is in the L2 and tile r-1 may be counted (a wavefront that has
+//    nothing to load in round r waits explicitly);
+//  * what the additions to the layers' counts return (did this one complete the
+//    layer?) is looked at in the round after.
+// So a layer's completion is noticed two tile times (about 10 us) after its last
+// store.  Layer 0, the layer the next forward pass needs first, does not pay
+// that: its tiles are marked urgent, every wavefront waits for its stores before
+// the barrier, and the count is added and looked at in the same round.  A
+// workgroup that finds no further tile (or would have to wait for the queue to
+// grow) first runs a DRAIN round -- wait for all stores, count what is uncounted,
+// look at every result -- so nothing is left hanging while it waits or leaves.
+// Turning a tile number into addresses costs no memory access: the leader keeps
+// the run it is working in in scalar registers and a copy of the run table in
+// LDS (a search of LDS at a run boundary).
 //
 // Control flow: branches on the wave index and on leader state are scalar (whole
 // wavefronts take them); the few single-lane sections are guarded by opaque
@@ -1461,21 +1469,24 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
     cur.grid_off = cur.layer = 0;
     cur.tile0 = cur.tile_end = 0u;     // empty: the first number goes through locate_run
     uint32_t r_next = 0u, r_have = 0u;
-    int pend_layer = 0, pend_tiles = 0;   // finished tiles of one layer not yet added to its count
+    uint32_t k_wait = 0u;                 // the tile number a DRAIN round has to find work for
+    int prev_n = 0, prev_layer = 0;       // the tile of the round before: streamed, not counted yet (prev_n = 0: none)
+    bool prev_long = false;
+    int pend_layer = 0, pend_tiles = 0;   // counted tiles of one long run not yet added to their layer's count
     uint32_t pend_cnt = 0u;               // their elements
-    // retire counts that have been added but whose result (did this addition complete the layer?) has not
-    // been looked at yet: A = a layer the workgroup has left, B = the layer of the tile just finished
+    // additions that have been made but whose result (did this one complete the layer?) has not been looked
+    // at yet: A = a layer the workgroup has left, B = the layer of the tile counted last
     unsigned long long po_old_a = 0ull, po_old_b = 0ull;      // vector registers: what the additions return
     unsigned long long po_le_a = 1ull, po_le_b = 1ull;        // vector registers: elements of the layers (loaded with
                                                               // the additions, so that nothing waits for them alone)
     uint32_t po_cnt_a = 0u, po_cnt_b = 0u;                    // what was added (0: nothing outstanding)
     int po_layer_a = 0, po_layer_b = 0;
-    // Look at the outstanding results; a count that completed its layer starts the layer's publication.
+    // Look at the outstanding results; an addition that completed its layer starts the layer's publication.
     auto settle = [&]() {
         if (po_cnt_a != 0u) {
             const unsigned long long old = uni(po_old_a);
             if (old + static_cast<unsigned long long>(po_cnt_a) == uni(po_le_a)) {
-                if (old == 0ull) complete_alone(fc, po_layer_a, lane);
+                if (old == 0ull && po_layer_a == 0) complete_alone(fc, po_layer_a, lane);
                 else complete_layer(fc, po_layer_a, xcd, lane);
             }
             po_cnt_a = 0u;
@@ -1483,31 +1494,79 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
         if (po_cnt_b != 0u) {
             const unsigned long long old = uni(po_old_b);
             if (old + static_cast<unsigned long long>(po_cnt_b) == uni(po_le_b)) {
-                if (old == 0ull) complete_alone(fc, po_layer_b, lane);
+                if (old == 0ull && po_layer_b == 0) complete_alone(fc, po_layer_b, lane);
                 else complete_layer(fc, po_layer_b, xcd, lane);
             }
             po_cnt_b = 0u;
         }
     };
+    // Count a tile whose stores have all been acknowledged (nothing may be outstanding: settle() first).
+    // In a long run (a layer of thousands of tiles, whose count is one word that every workgroup adds to) a
+    // workgroup adds P3_RETIRE_BATCH tiles at a time: fewer, larger additions.  In a short run every tile is
+    // added at once.  `flush`: add whatever is pending, too.
+    auto count_tile = [&](int t_layer, int t_n, bool t_long, bool flush) {
+        uint32_t cnt_a = 0u, cnt_b = 0u;
+        int layer_a = t_layer;
+        if (pend_tiles > 0 && pend_layer != t_layer) {
+            cnt_a = pend_cnt;
+            layer_a = pend_layer;
+            pend_cnt = 0u;
+            pend_tiles = 0;
+        }
+        if (t_n > 0) {
+            pend_cnt += static_cast<uint32_t>(t_n);
+            pend_tiles += 1;
+            pend_layer = t_layer;
+        }
+        if (pend_tiles > 0 && (flush || !t_long || pend_tiles >= P3_RETIRE_BATCH)) {
+            cnt_b = pend_cnt;
+            pend_cnt = 0u;
+            pend_tiles = 0;
+        }
+        if (cnt_a != 0u) {
+            if (lane_is(lane, 0))
+                po_old_a = __hip_atomic_fetch_add(&a.layer_done[layer_a], static_cast<unsigned long long>(cnt_a),
+                                                  __ATOMIC_RELAXED, P3_AGENT);
+            po_le_a = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.layers[layer_a].elems),
+                                        __ATOMIC_RELAXED, P3_AGENT);
+            po_cnt_a = cnt_a;
+            po_layer_a = layer_a;
+        }
+        if (cnt_b != 0u) {
+            if (lane_is(lane, 0))
+                po_old_b = __hip_atomic_fetch_add(&a.layer_done[pend_layer], static_cast<unsigned long long>(cnt_b),
+                                                  __ATOMIC_RELAXED, P3_AGENT);
+            po_le_b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.layers[pend_layer].elems),
+                                        __ATOMIC_RELAXED, P3_AGENT);
+            po_cnt_b = cnt_b;
+            po_layer_b = pend_layer;
+        }
+    };
+    // Take over the run `f` found.
+    auto enter_run = [&](const P3Run& r) {
+        cur.start = static_cast<int64_t>(uni(static_cast<unsigned long long>(r.start)));
+        cur.len = static_cast<int64_t>(uni(static_cast<unsigned long long>(r.len)));
+        cur.grid_off = uni(r.grid_off);
+        cur.layer = uni(r.layer);
+        cur.tile0 = uni(r.tile0);
+        cur.tile_end = uni(r.tile_end);
+    };
+    // The descriptor of tile k of the current run.  Tiles of layer 0 in a short run are urgent.
+    auto describe = [&](uint32_t k) {
+        P3TileDesc d = p3_tile_of_run(cur, k, a.tile_elems);
+        const bool long_run = cur.tile_end - cur.tile0 >= P3_LONG_RUN_TILES_PER_WG * a.n_blocks;
+        d.flags = (cur.layer == 0 && !long_run) ? P3T_URGENT : 0;
+        return d;
+    };
 
+    // The first round is a DRAIN round with nothing to drain: it finds the tile of the first number.
     if (wave == 0) {
-        const uint32_t k = uni(take_ticket(ctl, lane));
-        const Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, r_next, r_have, t_enter, lane, true);
-        r_next = uni(f.r_next);
-        r_have = uni(f.r_have);
+        k_wait = uni(take_ticket(ctl, lane));
         P3TileDesc d0;
         d0.start = 0;
-        d0.n = P3T_END;
+        d0.n = P3T_DRAIN;
         d0.layer = 0;
-        if (uni(f.found) != 0) {
-            cur.start = static_cast<int64_t>(uni(static_cast<unsigned long long>(f.run.start)));
-            cur.len = static_cast<int64_t>(uni(static_cast<unsigned long long>(f.run.len)));
-            cur.grid_off = uni(f.run.grid_off);
-            cur.layer = uni(f.run.layer);
-            cur.tile0 = uni(f.run.tile0);
-            cur.tile_end = uni(f.run.tile_end);
-            d0 = p3_tile_of_run(cur, k, a.tile_elems);
-        }
+        d0.flags = 0;
         if (lane_is(lane, 0)) s_desc = d0;
     }
     __syncthreads();
@@ -1515,152 +1574,104 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
     for (;;) {
         const int32_t n = uni(s_desc.n);                      // scalar: uniform branches
         if (n == P3T_END) break;
+        if (n == P3T_DRAIN) {
+            // every store of this workgroup is acknowledged; the leader counts what is uncounted, looks at
+            // every result, and only then looks (and, if need be, waits) for work
+            wait_vm_done();
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __syncthreads();
+            if (wave == 0) {
+                settle();
+                count_tile(prev_layer, prev_n, prev_long, true);
+                prev_n = 0;
+                settle();
+                const Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k_wait, r_next, r_have, t_enter, lane, true);
+                r_next = uni(f.r_next);
+                r_have = uni(f.r_have);
+                P3TileDesc dn;
+                dn.start = 0;
+                dn.n = P3T_END;
+                dn.layer = 0;
+                dn.flags = 0;
+                if (uni(f.found) == 1) {
+                    enter_run(f.run);
+                    dn = describe(k_wait);
+                }
+                if (lane_is(lane, 0)) s_desc = dn;
+            }
+            __syncthreads();
+            continue;
+        }
         const int64_t start = static_cast<int64_t>(uni(static_cast<unsigned long long>(s_desc.start)));
         const int32_t layer = uni(s_desc.layer);
+        const bool urgent = uni(s_desc.flags) != 0;
 
-        process_tile<WT, BF16>(gp, a.W, a.w, a.m, start, n, h);
+        const int32_t nvec = process_tile<WT, BF16>(gp, a.W, a.w, a.m, start, n, h);
 
-        // When to ask for the next tile number.  Last of all, after the stores are out, is best for a long
-        // drain: the exposed round trip paces the stream at the rate the memory takes (VGG-19, fp32: 1.021 ms
-        // against 1.044 when the number is asked for here, before the wait for the stores; hiding the trip and
-        // taking lanes away to compensate never beat it either).  A short drain is another matter: with 30
-        // tiles per workgroup (ResNet-50) the early number is 2.6 % faster, so the host asks for it when a
-        // workgroup gets fewer than 48 tiles.  With bf16 copies (twice as many, half as large loads per
-        // tile) the early number is better at every size (1.066 against 1.091 ms on VGG-19 with 16 copies).
-        const bool early = BF16 ? true : a.early_number != 0;
+        // the next tile number and this XCD's write-back line: asked for now, looked at behind the barrier
         uint32_t tk_pre = 0u;
         u32x4 fv_pre = {0u, 0u, 0u, 0u};
-        if (early && wave == 0) {
+        if (wave == 0) {
             if (lane_is(lane, 0)) tk_pre = __hip_atomic_fetch_add(&ctl->ticket, 1u, __ATOMIC_RELAXED, P3_AGENT);
             fv_pre = load_flush_view(ctl, xcd);
         }
-        // the write-through stores of this wavefront have been acknowledged (they are in this XCD's L2)
-        wait_vm_done();
+        // a wavefront that loaded nothing in this round has not waited for its earlier stores yet; the stores
+        // of an urgent tile are waited for at once
+        if (urgent || wave * 64 >= nvec) wait_vm_done();
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __syncthreads();                                      // everyone's stores are out: the tile may be retired
+        __syncthreads();                                      // every store of the tile before this one is out
 
         if (wave == 0) {
-            // What the additions of the previous round returned has long arrived (a whole tile was streamed
-            // meanwhile): look at it now.
-            settle();
-            // Counting finished tiles against their layer.  In a long run (a layer of thousands of tiles,
-            // whose count is one word that every workgroup adds to) a workgroup adds P3_RETIRE_BATCH tiles
-            // at a time: fewer, larger additions.  In a short run every tile is added at once: a workgroup
-            // gets a tile or two of such a run, and a count left pending would cost a round trip of its own
-            // when the next number falls into another run.  Counts of a layer the workgroup has left (A)
-            // and of the layer of this tile (B) travel together.
-            uint32_t cnt_a = 0u, cnt_b = 0u;
-            int layer_a = layer;
-            if (pend_tiles > 0 && pend_layer != layer) {
-                cnt_a = pend_cnt;
-                layer_a = pend_layer;
-                pend_cnt = 0u;
-                pend_tiles = 0;
-            }
-            pend_cnt += static_cast<uint32_t>(n);
-            pend_tiles += 1;
-            pend_layer = layer;
+            settle();                                         // what the additions of the round before returned
+            count_tile(prev_layer, prev_n, prev_long, false); // the tile of the round before
             const bool long_run = cur.tile_end - cur.tile0 >= P3_LONG_RUN_TILES_PER_WG * a.n_blocks;
-            if (!long_run || pend_tiles >= P3_RETIRE_BATCH) {
-                cnt_b = pend_cnt;
-                pend_cnt = 0u;
-                pend_tiles = 0;
+            prev_n = n;
+            prev_layer = layer;
+            prev_long = long_run;
+            const uint32_t k = uni(tk_pre);
+            const FlushView fv = view_of(fv_pre);
+            if (urgent) {                                     // count it and look at the result now
+                settle();
+                count_tile(layer, n, long_run, true);
+                prev_n = 0;
+                settle();
             }
-            if (cnt_a != 0u) {
-                if (lane_is(lane, 0))
-                    po_old_a = __hip_atomic_fetch_add(&a.layer_done[layer_a], static_cast<unsigned long long>(cnt_a),
-                                                      __ATOMIC_RELAXED, P3_AGENT);
-                po_le_a = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.layers[layer_a].elems),
-                                            __ATOMIC_RELAXED, P3_AGENT);
-                po_cnt_a = cnt_a;
-                po_layer_a = layer_a;
-            }
-            if (cnt_b != 0u) {
-                if (lane_is(lane, 0))
-                    po_old_b = __hip_atomic_fetch_add(&a.layer_done[layer], static_cast<unsigned long long>(cnt_b),
-                                                      __ATOMIC_RELAXED, P3_AGENT);
-                po_le_b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.layers[layer].elems),
-                                            __ATOMIC_RELAXED, P3_AGENT);
-                po_cnt_b = cnt_b;
-                po_layer_b = layer;
-            }
-            // The next tile number.  Asked for now (late), its round trip is exposed and the additions above
-            // ride on it: their results are there when the number is, and are looked at right away.  Asked
-            // for before the wait for the stores (early), it is here already, and nothing in this section
-            // waits for memory: the results of the additions are looked at one round later -- except for
-            // layer 0, the layer the next forward pass needs first, which never waits a round.
-            uint32_t tk_v = tk_pre;
-            u32x4 fv_v = fv_pre;
-            if (!early) {
-                if (lane_is(lane, 0)) tk_v = __hip_atomic_fetch_add(&ctl->ticket, 1u, __ATOMIC_RELAXED, P3_AGENT);
-                fv_v = load_flush_view(ctl, xcd);
-            }
-            const uint32_t k = uni(tk_v);
-            const FlushView fv = view_of(fv_v);
-            if (!early || (po_cnt_a != 0u && po_layer_a == 0) || (po_cnt_b != 0u && po_layer_b == 0)) settle();
             if (flush_due(fv, false)) serve_flush(fc, fv.req, xcd, lane);
 
-            bool found = true;
-            if (k >= cur.tile_end) {                          // left the run (or there was none yet)
-                if (pend_tiles > 0) {                         // (only at the end of a long run)
-                    post_retire(fc, a.layer_done, a.layers, pend_layer, pend_cnt, xcd, lane);
-                    pend_cnt = 0u;
-                    pend_tiles = 0;
-                }
-                // The usual case, here in line: the run is one of the next 64 of the LDS copy (tile numbers and
-                // runs both only grow, so it is the first whose end lies beyond the number).  Everything else --
-                // a longer search, a refill of the copy, a wait for the queue to grow -- is the out-of-line
-                // function's business (calling it costs about a microsecond of argument traffic alone).
-                P3Run hit_run = cur;
-                bool hit = false;
-                if (r_next < r_have) {
-                    const uint32_t r = r_next + static_cast<uint32_t>(lane);
-                    const bool in = r < r_have;
-                    uint32_t te = 0u;
-                    if (in) te = s_runs[r & (P3_RUN_CACHE - 1)].tile_end;
-                    const unsigned long long hits = __ballot(in && k < te);
-                    if (hits != 0ull) {
-                        const uint32_t rf = r_next + static_cast<uint32_t>(__builtin_ctzll(hits));
-                        hit_run = s_runs[rf & (P3_RUN_CACHE - 1)];          // every lane reads the same entry
-                        r_next = rf + 1u;
-                        hit = true;
-                    }
-                }
-                if (!hit) {
-                    Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, r_next, r_have, t_enter, lane, false);
-                    if (uni(f.found) == 2) {
-                        // the queue has to grow first: nothing stays unlooked-at while the workgroup waits
-                        settle();
-                        f = locate_run<WAIT>(qc, fc, xcd, s_runs, k, uni(f.r_next), uni(f.r_have), t_enter, lane, true);
-                    }
-                    r_next = uni(f.r_next);
-                    r_have = uni(f.r_have);
-                    found = uni(f.found) == 1;
-                    hit_run = f.run;
-                }
-                if (found) {
-                    cur.start = static_cast<int64_t>(uni(static_cast<unsigned long long>(hit_run.start)));
-                    cur.len = static_cast<int64_t>(uni(static_cast<unsigned long long>(hit_run.len)));
-                    cur.grid_off = uni(hit_run.grid_off);
-                    cur.layer = uni(hit_run.layer);
-                    cur.tile0 = uni(hit_run.tile0);
-                    cur.tile_end = uni(hit_run.tile_end);
-                }
-            }
             P3TileDesc dn;
             dn.start = 0;
-            dn.n = P3T_END;
+            dn.n = P3T_DRAIN;                                 // unless the tile is found below
             dn.layer = 0;
-            if (found) dn = p3_tile_of_run(cur, k, a.tile_elems);
+            dn.flags = 0;
+            k_wait = k;
+            if (k < cur.tile_end) {
+                dn = describe(k);
+            } else if (r_next < r_have) {
+                // Left the run.  The usual case, here in line: the next run is one of the next 64 of the LDS
+                // copy (tile numbers and runs both only grow, so it is the first whose end lies beyond the
+                // number).  Everything else -- a refill of the copy, a wait for the queue to grow, the end
+                // of the queue -- is left to a DRAIN round.
+                const uint32_t r = r_next + static_cast<uint32_t>(lane);
+                const bool in = r < r_have;
+                uint32_t te = 0u;
+                if (in) te = s_runs[r & (P3_RUN_CACHE - 1)].tile_end;
+                const unsigned long long hits = __ballot(in && k < te);
+                if (hits != 0ull) {
+                    const uint32_t rf = r_next + static_cast<uint32_t>(__builtin_ctzll(hits));
+                    enter_run(s_runs[rf & (P3_RUN_CACHE - 1)]);          // every lane reads the same entry
+                    r_next = rf + 1u;
+                    dn = describe(k);
+                } else {
+                    r_next = r_have - r_next > 64u ? r_next + 64u : r_have;
+                }
+            }
             if (lane_is(lane, 0)) s_desc = dn;                // everyone has read the old one before the barrier above
         }
         __syncthreads();                                      // the next descriptor is in LDS
     }
 
-    if (wave == 0) {
-        settle();                                             // the additions of the last round
-        leave_loop(fc, xcd, lane);
-    }
+    // (the loop ends behind a DRAIN round: nothing uncounted, nothing unlooked-at)
+    if (wave == 0) leave_loop(fc, xcd, lane);
 
     // Last workgroup out re-arms the per-launch words for the next drain.
     if (lane_is(tid, 0)) {

@@ -18,9 +18,6 @@
 #define P3_LONG_RUN_TILES_PER_WG 8u // a run is long when it gives every workgroup at least this many tiles
 #define P3_PUBLISHED 0x80000000u   // layer_req: the layer's done flag has been written
 #define P3_FLUSH_GAP_TICKS 5000u   // busy workgroups leave 50 us (100 MHz clock) between two write-backs of one L2
-#ifndef P3_EARLY_BELOW_TILES_PER_WG
-#define P3_EARLY_BELOW_TILES_PER_WG 48   // drains of fewer tiles per workgroup draw their tile numbers before the wait for the stores
-#endif
 #define P3_INLINE_MARKS 256      // marks handed to a SNAPSHOT/TICKED drain with its launch arguments
 
 // Device-side status of a drain (written to pinned host memory at its end).
@@ -155,7 +152,6 @@ struct P3DrainArgs {
     uint32_t n_blocks;
     int32_t W;
     float lr, mu, rescale, wd;
-    int32_t early_number;         // leaders ask for the next tile number before they wait for their stores (short drains)
     // SNAPSHOT/TICKED: the marks this drain has to fold, in mark order, when they fit
     // (else n_inline = 0 and the kernel reads the pinned mark log over the host link)
     int32_t n_inline;

@@ -768,8 +768,6 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
     a.mu = p->mu;
     a.rescale = p->rescale;
     a.wd = p->wd;
-    // short drains (fewer than 48 tiles per workgroup) draw their tile numbers early (see run_worker)
-    a.early_number = p->tiles_total < P3_EARLY_BELOW_TILES_PER_WG * static_cast<int64_t>(p->grid) ? 1 : 0;
     a.n_inline = 0;
     if (p->mode != P3_MODE_LIVE && !p->stream_marks && limit - p->drained_upto <= P3_INLINE_MARKS) {
         std::lock_guard<std::mutex> lk(p->mu_host);
@@ -1233,7 +1231,6 @@ extern "C" int p3_drain_static(const p3_plan_t* p, int32_t W, const void* const*
         a.mu = mu;
         a.rescale = rescale;
         a.wd = wd;
-        a.early_number = tiles < P3_EARLY_BELOW_TILES_PER_WG * static_cast<int64_t>(grid) ? 1 : 0;
         a.n_inline = n_ready;
         for (int32_t i = 0; i < n_ready; ++i) a.inline_marks[i] = ready_layers[i];
         P3GradPtrs gp;

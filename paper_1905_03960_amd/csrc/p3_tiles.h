@@ -35,10 +35,13 @@ struct P3Run {
 // What a workgroup works on in one round (LDS only).
 struct P3TileDesc {
     int64_t start;        // element offset into the arenas
-    int32_t n;            // elements, or P3T_END
+    int32_t n;            // elements, or P3T_END / P3T_DRAIN
     int32_t layer;        // owning layer
+    int32_t flags;        // P3T_URGENT or 0
+    int32_t pad;
 };
-enum { P3T_END = -1 };
+enum { P3T_END = -1, P3T_DRAIN = -2 };   // no more work / a round without a tile (see the worker loop)
+enum { P3T_URGENT = 1 };                 // the tile's completion is counted in its own round
 
 // Grid cells (= tiles) that the stretch [start, start+len) touches; len >= 1.
 P3_HD int64_t p3_run_cells(int64_t start, int64_t len, int32_t tile_elems) {
@@ -68,6 +71,8 @@ P3_HD P3TileDesc p3_tile_of_run(const P3Run& r, uint32_t k, int32_t tile_elems) 
     d.start = lo;
     d.n = static_cast<int32_t>(hi - lo);
     d.layer = r.layer;
+    d.flags = 0;
+    d.pad = 0;
     return d;
 }
 
