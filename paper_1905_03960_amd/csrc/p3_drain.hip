@@ -79,6 +79,18 @@ __device__ __forceinline__ void pin_here(unsigned long long& v) { asm volatile("
 // this wait before the barrier.
 __device__ __forceinline__ void wait_vm_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// The device's constant-rate clock (100 MHz), read where the program says and every time it says: as an
+// intrinsic the read may be moved out of a loop by the compiler (it has no operands), which would turn
+// every time limit in this file into a constant.  Costs about as much as a trip to memory.
+__device__ __forceinline__ uint64_t clock_now() {
+    uint64_t t;
+    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t) : : "memory");
+    return t;
+}
+
+// Wait for this wavefront's LDS (and scalar-memory) operations only.
+__device__ __forceinline__ void wait_lds_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 // Hyper-parameters as the kernel sees them.  Whether weight decay takes part is
 // a compile-time property of the kernel: a run-time test between the loads and
 // the arithmetic of every vector was measured to cost 12 % of the stream's
@@ -424,7 +436,7 @@ __device__ __attribute__((noinline)) void publish_flushed(FlushCtx a, int lane) 
                 if (__hip_atomic_compare_exchange_strong(&a.layer_req[l], &v, v | P3_PUBLISHED, __ATOMIC_RELAXED,
                                                          __ATOMIC_RELAXED, P3_AGENT)) {
                     a.t_seen[l] = __hip_atomic_load(&a.t_seen_dev[l], __ATOMIC_RELAXED, P3_AGENT);
-                    a.t_done[l] = wall_clock64();
+                    a.t_done[l] = clock_now();
                     __hip_atomic_store(&a.done_flag[l], a.iter_seq, __ATOMIC_RELEASE, P3_SYSTEM);
                 }
             }
@@ -457,7 +469,7 @@ __device__ __forceinline__ FlushView view_of(u32x4 v) {
 __device__ __forceinline__ bool flush_due(const FlushView& f, bool idle) {
     if (f.req <= f.claim) return false;
     if (idle || f.urgent > f.claim) return true;
-    return static_cast<uint32_t>(wall_clock64()) - f.time32 >= P3_FLUSH_GAP_TICKS;
+    return static_cast<uint32_t>(clock_now()) - f.time32 >= P3_FLUSH_GAP_TICKS;
 }
 
 // Round `want` is open: write this XCD's L2 back unless another of its workgroups has undertaken to.
@@ -466,7 +478,7 @@ __device__ __attribute__((noinline)) void serve_flush(FlushCtx a, uint32_t want,
     if (lane_is(lane, 0)) c = __hip_atomic_fetch_max(&a.ctl->xcd[xcd].claim, want, __ATOMIC_RELAXED, P3_AGENT);
     if (uni(c) >= want) return;
     if (lane_is(lane, 0))
-        __hip_atomic_store(&a.ctl->xcd[xcd].time32, static_cast<uint32_t>(wall_clock64()), __ATOMIC_RELAXED, P3_AGENT);
+        __hip_atomic_store(&a.ctl->xcd[xcd].time32, static_cast<uint32_t>(clock_now()), __ATOMIC_RELAXED, P3_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     uint32_t o = 0u;
     if (lane_is(lane, 0)) o = __hip_atomic_fetch_max(&a.ctl->xcd[xcd].ack, want, __ATOMIC_RELAXED, P3_AGENT);
@@ -505,7 +517,7 @@ __device__ __attribute__((noinline)) void complete_alone(FlushCtx a, int layer, 
     if (lane_is(lane, 0)) {
         __hip_atomic_store(&a.layer_req[layer], P3_PUBLISHED, __ATOMIC_RELAXED, P3_AGENT);
         a.t_seen[layer] = __hip_atomic_load(&a.t_seen_dev[layer], __ATOMIC_RELAXED, P3_AGENT);
-        a.t_done[layer] = wall_clock64();
+        a.t_done[layer] = clock_now();
         __hip_atomic_store(&a.done_flag[layer], a.iter_seq, __ATOMIC_RELEASE, P3_SYSTEM);
     }
 }
@@ -559,6 +571,7 @@ struct SelectorLds {
     // folding marks and taking the lowest bits then cost LDS latencies instead of trips to memory
     unsigned long long bm[P3_LDS_BM_WORDS];
     uint8_t lstate[P3_LDS_LAYERS];
+    P3LayerDev pre[P3_INLINE_MARKS];       // table entries of the layers whose marks came with the launch, in mark order
     int32_t nb;                            // slices in this step
     int32_t done;
     int32_t overflow;                      // set by a single-wavefront step that found the queue full
@@ -624,18 +637,21 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
 // after the call covers all of them, so folding 64 marks costs one trip to
 // memory instead of 64.  The bitmap is only ever touched with atomic
 // operations, so all accesses meet at the same level of the memory system.
+// `pre`: the layer's table entry if it has been fetched already (else it is loaded here: a trip to memory).
+// `now`: the device clock as read at the top of the selection round (reading it costs about as much as a
+// trip to memory, so it is read once per round, not once per use).
 __device__ __forceinline__ void fold_lanes(const P3DrainArgs& a, unsigned long long* bm, uint8_t* ls, bool active,
-                                           int layer, SelState& st) {
+                                           int layer, SelState& st, const P3LayerDev* pre, uint64_t now) {
     int count = 0, first = 0, end = 0;
     uint32_t w0 = 0xffffffffu;
     if (active) {
-        const P3LayerDev ld = a.layers[layer];
+        const P3LayerDev ld = pre ? *pre : a.layers[layer];
         first = ld.first;
         end = ld.first + ld.count;
         w0 = static_cast<uint32_t>(first >> 6);
         ls[layer] = P3L_RELEASED;
         // device memory (the selector never waits on the host link), written through for the worker that reads it
-        __hip_atomic_store(&a.t_seen_dev[layer], wall_clock64(), __ATOMIC_RELAXED, P3_AGENT);
+        __hip_atomic_store(&a.t_seen_dev[layer], now, __ATOMIC_RELAXED, P3_AGENT);
         count = ld.count;
     }
     // the words [from, to] of the range [first, end) that this lane ORs in, `step` apart
@@ -725,7 +741,7 @@ __device__ __forceinline__ int take_lowest(const P3DrainArgs& a, unsigned long l
 // ticks (backward order).  Writes `want` (or fewer, if the ready layers run out) slice ids to
 // lds.batch.  One wavefront.
 __device__ __forceinline__ int take_fifo(const P3DrainArgs& a, uint8_t* ls, SelectorLds& lds, int want, int lane,
-                                         SelState& st) {
+                                         SelState& st, uint64_t now) {
     int nb = 0;
     while (nb < want) {
         if (st.cur_left == 0u) {
@@ -756,7 +772,7 @@ __device__ __forceinline__ int take_fifo(const P3DrainArgs& a, uint8_t* ls, Sele
                 if (nl < 0) break;
                 if (lane_is(lane, 0)) {
                     ls[nl] = P3L_RELEASED;
-                    __hip_atomic_store(&a.t_seen_dev[nl], wall_clock64(), __ATOMIC_RELAXED, P3_AGENT);
+                    __hip_atomic_store(&a.t_seen_dev[nl], now, __ATOMIC_RELAXED, P3_AGENT);
                 }
                 st.pending -= 1u;
             } else {
@@ -783,7 +799,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: whole wavefronts branch on it
     P3Ctl* ctl = a.ctl;
 
-    const uint64_t t_entry = wall_clock64();
+    const uint64_t t_entry = clock_now();
     // Memory ordering.  A store's acknowledgement (what `s_waitcnt vmcnt(0)` waits for; a
     // workgroup-scope fence waits for nothing here) only says that the store has reached the L2
     // of the issuing XCD; other XCDs see it once that L2 has written it back, and only an
@@ -819,7 +835,19 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             ctl->cur_next = ctl->cur_left = 0u;
         }
     }
+    // The table entries of the layers whose marks came with the launch are asked for now, all at once (one
+    // thread per mark), so that the wait below covers them too: folding the marks then needs no trip to
+    // memory (it used to take one per 64 marks, each behind the other).
+    const bool pre_ok = a.n_inline > 0;
+    P3LayerDev pre_mine;
+    pre_mine.first = pre_mine.count = 0;
+    pre_mine.elems = 0;
+    if (pre_ok && tid < a.n_inline) {
+        const int32_t l = a.inline_marks[tid];
+        if (l >= 0 && l < a.L) pre_mine = a.layers[l];
+    }
     wait_vm_done();                     // the cleared counts are in the L2 before anybody can add to them
+    if (pre_ok && tid < a.n_inline) lds.pre[tid] = pre_mine;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
 
@@ -864,6 +892,8 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             //     waited for (bounded by the watchdog).  LIVE: whatever has arrived.
             uint64_t lim = a.epoch_limit;
             if (a.mode == 1) lim = a.epoch_base + static_cast<uint64_t>(a.L);
+            // the device clock, once per round (the first round makes do with the stamp taken at entry)
+            const uint64_t t_round = rounds == 0u ? t_entry : clock_now();
             // LIVE: everything a round needs from outside the CU -- the next entries of the mark log and the
             // stop flag (both over the host link), this XCD's write-back line, the workers' tile counter -- is
             // asked for at once, one wait instead of four in a row (a selection step took 7.5 us, half of
@@ -886,10 +916,14 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                 const uint64_t base = a.epoch_base + st.marks_applied;
                 int n_new = lim - base > 64 ? 64 : static_cast<int>(lim - base);
                 int my_layer = -1;
+                uint32_t pre_idx = 0u;
                 if (a.n_inline > 0) {        // came with the launch: marks_applied counts from inline_marks[0]
                     if (lane < n_new) {
                         const uint32_t idx = st.marks_applied - inline_first + static_cast<uint32_t>(lane);
-                        if (idx < static_cast<uint32_t>(a.n_inline)) my_layer = a.inline_marks[idx];
+                        if (idx < static_cast<uint32_t>(a.n_inline)) {
+                            my_layer = a.inline_marks[idx];
+                            pre_idx = idx;
+                        }
                     }
                 } else {
                     bool there = false;
@@ -909,7 +943,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                     if (n_new == 0) {
                         if (a.mode == 1) break;                       // LIVE: nothing new now
                         // a mark that a stream has yet to make: wait for it, within the drain's time limit
-                        if (wall_clock64() - t_start > a.watchdog_ticks ||
+                        if (clock_now() - t_start > a.watchdog_ticks ||
                             __hip_atomic_load(&a.hs->abort_flag, __ATOMIC_RELAXED, P3_SYSTEM) != 0u) {
                             gave_up = true;
                             break;
@@ -931,7 +965,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                             ls[my_layer] = P3L_RELEASED;
                             const uint32_t pos = st.fifo_tail + static_cast<uint32_t>(__popcll(oks & ((1ull << lane) - 1ull)));
                             __hip_atomic_store(&a.fifo[pos], my_layer, __ATOMIC_RELAXED, P3_AGENT);
-                            __hip_atomic_store(&a.t_seen_dev[my_layer], wall_clock64(), __ATOMIC_RELAXED, P3_AGENT);
+                            __hip_atomic_store(&a.t_seen_dev[my_layer], t_round, __ATOMIC_RELAXED, P3_AGENT);
                         }
                     }
                     st.n_ready += static_cast<uint32_t>(wave_sum_i32(cnt));
@@ -941,12 +975,25 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                     if (ok) ls[my_layer] = P3L_PENDING;
                     st.pending += static_cast<uint32_t>(__popcll(__ballot(ok)));
                 } else {
-                    fold_lanes(a, bm, ls, ok, my_layer, st);
+                    // (marks read over the host link: the stamp is taken now, the read of the clock hides behind
+                    // the link's latency; marks that came with the launch carry the round's stamp)
+                    fold_lanes(a, bm, ls, ok, my_layer, st, pre_ok ? &lds.pre[pre_idx] : nullptr,
+                               a.n_inline > 0 ? t_round : clock_now());
                 }
                 st.marks_applied += static_cast<uint32_t>(n_new);
                 folded_now = true;
-                if (!in_lds) wait_vm_done();                              // a bitmap in memory: the ORs have been performed
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the ORs have landed
+                // the ORs have landed (a bitmap in LDS: nothing here waits for memory -- the stamps stored by
+                // fold_lanes are covered by the release fence in front of the next publication)
+                if (in_lds) wait_lds_done();
+                else {
+                    wait_vm_done();
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                }
+                // LIVE: look again only if this look came back full (then more marks may be waiting behind
+                // it).  A host that marks layer after layer without a pause would otherwise keep this loop
+                // going -- every look finds another mark or two -- and nothing would be claimed until the
+                // last mark is in: what is ready is served while the rest arrives.
+                if (a.mode == 1 && n_new < 64) break;
             }
             // a short first step gets the workers going; later steps amortise the publication
             // (as many slices as give every workgroup two tiles, at least what one wavefront groups on its own)
@@ -966,7 +1013,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                 if (flush_due(fv, true)) serve_flush(sel_fc, fv.req, sel_xcd, lane);
             }
             rounds += 1u;
-            const bool expired = wall_clock64() - t_start > a.watchdog_ticks;
+            const bool expired = t_round - t_start > a.watchdog_ticks;
             // (2) decide how many slices may be claimed now
             if (ab != 0u || expired || gave_up) {
                 done = true;
@@ -988,10 +1035,13 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                             if (r <= st.clock) rel = true;
                             else if (r < next) next = r;
                         }
-                        fold_lanes(a, bm, ls, rel, l, st);
+                        fold_lanes(a, bm, ls, rel, l, st, nullptr, t_round);
                         st.pending -= static_cast<uint32_t>(__popcll(__ballot(rel)));
-                        if (!in_lds) wait_vm_done();
-                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                        if (in_lds) wait_lds_done();
+                        else {
+                            wait_vm_done();
+                            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                        }
                     }
                     next = wave_min_i64(next);
                     if (st.n_ready == 0u && st.pending > 0u) {
@@ -1039,7 +1089,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                     st.status = P3D_OVERFLOW;
                     budget = 0;
                 } else {
-                    const int got = a.policy == 1 ? take_fifo(a, ls, lds, budget, lane, st)
+                    const int got = a.policy == 1 ? take_fifo(a, ls, lds, budget, lane, st, t_round)
                                                   : take_lowest(a, bm, lds, budget, lane, st);
                     if (got != budget) {         // bitmap and counter disagree: stop rather than spin
                         done = true;
@@ -1131,7 +1181,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                         __hip_atomic_store(&ctl->published, st.pub_runs, __ATOMIC_RELAXED, P3_AGENT);
                         if (first) {
                             a.hs->t_sel_enter = t_entry;
-                            a.hs->t_sel_first_pub = wall_clock64();   // first growth
+                            a.hs->t_sel_first_pub = clock_now();   // first growth
                             a.hs->phase = P3P_PUBLISHED;
                         }
                     }
@@ -1235,7 +1285,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                     __hip_atomic_store(&ctl->published, st.pub_runs, __ATOMIC_RELAXED, P3_AGENT);
                     if (first) {                       // (stores over the host link once per launch, not per step)
                         a.hs->t_sel_enter = t_entry;
-                        a.hs->t_sel_first_pub = wall_clock64();   // first growth
+                        a.hs->t_sel_first_pub = clock_now();   // first growth
                         a.hs->phase = P3P_PUBLISHED;
                     }
                 }
@@ -1270,7 +1320,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             a.hs->t_sel_enter = t_entry;
             a.hs->t_sel_first_pub = 0;
         }
-        a.hs->t_sel_final = wall_clock64();
+        a.hs->t_sel_final = clock_now();
         a.hs->phase = P3P_FINAL;
     }
     __syncthreads();
@@ -1328,6 +1378,7 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
     out.run.tile0 = 0u;
     out.run.tile_end = 0u;
     out.found = 0;
+    uint32_t looks = 0u;
     for (;;) {
         while (r_next < r_have) {
             const uint32_t r = r_next + static_cast<uint32_t>(lane);
@@ -1399,7 +1450,9 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
         }
         // bounded wait: the selector turns a host abort into `final_runs`, so the workers
         // only need the clock (no host-memory reads from hundreds of spinners)
-        if (wall_clock64() - t_enter > a.watchdog_ticks) {
+        // (reading the clock costs as much as a look at the queue: every 16th look is enough for a limit of seconds)
+        looks += 1u;
+        if ((looks & 15u) == 0u && clock_now() - t_enter > a.watchdog_ticks) {
             if (lane_is(lane, 0)) a.hs->worker_status = P3D_WATCHDOG;
             break;
         }
@@ -1458,7 +1511,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: whole wavefronts branch on it
     P3Ctl* ctl = a.ctl;
     const HyperT<WD> h = {a.lr, a.mu, a.rescale, a.wd};
-    const uint64_t t_enter = wall_clock64();
+    const uint64_t t_enter = clock_now();
     const QueueCtx qc = {a.ctl, a.runq, a.hs, a.watchdog_ticks, a.arena_elems, a.L, a.tile_elems};
     const FlushCtx fc = {a.ctl, a.layer_req, a.t_seen_dev, a.t_seen, a.t_done, a.done_flag, a.iter_seq, a.L};
     const int xcd = xcd_of_this_wave();

@@ -675,11 +675,19 @@ int p3_mark_ready_on_stream(p3_plan_t* p, int32_t layer, void* producer_stream) 
 
 // The consumer's side of the same idea: a stream waits, on the device, until the layer's done flag
 // carries this iteration's number.  One lane polls the pinned flag; the wait is bounded.
+// (The clock is read with volatile inline assembly: as an intrinsic the read has no operands and may be
+// moved out of the loop, which would make the time limit a constant.)
+__device__ __forceinline__ unsigned long long wait_clock_now() {
+    unsigned long long t;
+    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t) : : "memory");
+    return t;
+}
+
 __global__ void p3_wait_kernel(const uint32_t* flag, uint32_t want, unsigned long long limit_ticks,
                                uint32_t* expired) {
-    const unsigned long long t0 = wall_clock64();
+    const unsigned long long t0 = wait_clock_now();
     while (__hip_atomic_load(flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) != want) {
-        if (wall_clock64() - t0 > limit_ticks) {
+        if (wait_clock_now() - t0 > limit_ticks) {
             __hip_atomic_store(expired, want, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             break;
         }

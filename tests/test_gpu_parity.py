@@ -90,7 +90,7 @@ def test_partial_iteration_and_empty_drain():
 
 # ------------------------------------------- ragged shapes, every W, both dtypes --
 RAGGED = [1, 3, 5, 10, 4097, 50001, 8191, 8192, 8193, 64, 63, 65, 12288, 2, 3583, 3584, 3585, 7169, 895, 897,
-          3327, 3328, 3329, 6657, 831, 833]          # around the default tile (832 lanes x 4) and its neighbours
+          3327, 3328, 3329, 6657, 831, 833, 3071, 3072, 3073, 6145, 767, 769]   # around the default tile (768 streaming lanes x 4), an earlier default, and their neighbours
 
 
 @pytest.mark.parametrize("bf16", [False, True])
