@@ -28,12 +28,11 @@ HBM_PEAK_GBPS = 8000.0
 
 
 # HBM bytes per launch of the drain kernel from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-# profiles/p3_drain_kernel_vgg19_fp32_hbm_traffic.md (already scaled by what the counters read for a plain
-# copy), valid for the kernel sources whose hash is given and for the default vgg19 workload only.
+# profiles/p3_drain_kernel_*_hbm_traffic.md (already scaled by what the counters read for a plain copy), valid
+# for the kernel sources whose hash is given, the workload's default slice size and the default launch shape.
 TRAFFIC = {
-    "sources_sha256": "dddce9141e1bef11a42ab556470dffccb9716d1b2c0c44a1f9da18a4b1719553",
-    "workload": "vgg19", "slice_elems": 50000,
-    "bytes_per_launch": 6913495433,
+    "sources_sha256": "861fd9123427242f48079b38f5717989d091c78750081a12b2eddb1eb7db000b",
+    "bytes_per_launch": {"vgg19": 6902762925, "vgg19_bf16": 6902798111},
 }
 
 
@@ -43,7 +42,7 @@ def kernel_source_hash():
     import re
     here = os.path.dirname(os.path.abspath(__file__))
     h = hashlib.sha256()
-    for f in ("p3_drain.hip", "p3_internal.h"):
+    for f in ("p3_drain.hip", "p3_internal.h", "p3_tiles.h"):
         with open(os.path.join(here, "paper_1905_03960_amd", "csrc", f), "r") as fh:
             text = fh.read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
@@ -52,15 +51,15 @@ def kernel_source_hash():
     return h.hexdigest()
 
 
-def measured_traffic(args, slice_elems):
+def measured_traffic(args, slice_elems, default_slice_elems):
     """Counter-measured HBM bytes per launch, or None once the kernel has changed since they were taken."""
     try:
         same_kernel = kernel_source_hash() == TRAFFIC["sources_sha256"]
     except OSError:
         return None
-    same = (same_kernel and args.workload == TRAFFIC["workload"] and slice_elems == TRAFFIC["slice_elems"]
-            and not args.tile_elems and not args.wgs_per_cu and args.shards == 1)
-    return TRAFFIC["bytes_per_launch"] if same else None
+    same = (same_kernel and slice_elems == default_slice_elems and not args.tile_elems and not args.wgs_per_cu
+            and not args.reserved_cus and args.shards == 1)
+    return (TRAFFIC["bytes_per_launch"].get(args.workload) or None) if same else None
 
 
 def overlap_study(b, torch, plan, sizes, stream, gemm_rows=2048, reps=5):
@@ -131,6 +130,50 @@ def overlap_study(b, torch, plan, sizes, stream, gemm_rows=2048, reps=5):
     return res
 
 
+def fixed_cost_study(b, torch, W=8, sizes_m=(24, 48, 96, 144), reps=12):
+    """What a launch costs beyond the bytes it moves: one-layer fp32 parameter sets of several sizes (arenas at
+    the suggested stride, one snapshot drain per iteration, kernel time from the library's HIP events), a
+    straight line through (bytes, kernel time): the slope is the rate at which the kernel streams once it is
+    under way, the intercept what every launch pays whatever its size (launch, first selection step, the last
+    tiles running out)."""
+    import numpy as np
+    pts = []
+    stream = torch.cuda.Stream()
+    for m in sizes_m:
+        n = m * 1000 * 1000
+        plan = b.p3_plan([n], 50000)
+        arena = b.p3_arena_elems(plan)
+        slot = b.p3_suggest_arena_stride(plan, b.P3_GRAD_FP32)
+        pool = torch.empty((W + 2) * slot + (1 << 21), dtype=torch.uint8, device="cuda")
+        v = [pool[i * slot:i * slot + arena * 4].view(torch.float32) for i in range(W + 2)]
+        for t in v[:W]:
+            t.normal_(0, 1e-3)
+        v[W].normal_(0, 0.05)
+        v[W + 1].zero_()
+        b.p3_bind(plan, [t.data_ptr() for t in v[:W]], b.P3_GRAD_FP32, v[W].data_ptr(), v[W + 1].data_ptr())
+        b.p3_set_hyper(plan, 0.1, 0.9)
+        for it in range(reps + 2):
+            if it == 2:
+                b.p3_sync(plan)
+                b.p3_profile_enable(plan, True)
+            b.p3_begin_iter(plan)
+            b.p3_mark_ready(plan, 0)
+            b.p3_drain(plan, stream.cuda_stream)
+        ms, cnt = b.p3_profile_read(plan)
+        b.p3_profile_enable(plan, False)
+        pts.append(((W * 4 + 16) * n, ms / cnt))
+        b.p3_destroy(plan)
+        del v, pool
+    x = np.array([p[0] for p in pts], dtype=np.float64)
+    y = np.array([p[1] for p in pts], dtype=np.float64)
+    slope, icpt = np.polyfit(x, y, 1)                 # ms per byte, ms
+    rate = 1.0 / slope / 1e6                          # GB/s
+    return {"what": f"one-layer fp32 sets, W={W}, kernel ms by HIP events, least-squares line",
+            "points": [{"bytes": int(p[0]), "kernel_ms": round(p[1], 4)} for p in pts],
+            "marginal_GBps": round(rate, 1), "marginal_frac": round(rate / HBM_PEAK_GBPS, 4),
+            "fixed_us_per_launch": round(icpt * 1e3, 1)}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +202,9 @@ def parse():
     ap.add_argument("--overlap", action="store_true",
                     help="also time the drain beside a synthetic backward pass (bf16 GEMMs on a producer stream "
                          "that marks each layer as its next operation); adds an 'overlap' object to the line")
+    ap.add_argument("--fixed-cost", action="store_true",
+                    help="add 'fixed_cost': drains of one-layer sets of several sizes, the rate at which the kernel "
+                         "streams once under way (slope) and what every launch pays whatever its size (intercept)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -248,18 +294,18 @@ def main():
         b.p3_mark_ready_many(plan, order)
         b.p3_drain(plan, stream.cuda_stream)
 
-    def probe(pl, n=8):
-        """Average kernel time of n drains on a placement (after two untimed ones)."""
+    def probe(pl, n=10):
+        """Median kernel time of n drains on a placement (after three untimed ones)."""
         bind(pl)
-        for _ in range(2):
+        for _ in range(3):
             step()
         b.p3_sync(plan)
         b.p3_profile_enable(plan, True)
         for _ in range(n):
             step()
-        ms, cnt = b.p3_profile_read(plan)
+        _, _, each = b.p3_profile_read(plan, each=n)
         b.p3_profile_enable(plan, False)
-        return ms / max(cnt, 1)
+        return float(np.median(each))
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -287,6 +333,9 @@ def main():
                  "timed_slot_MiB": round(first_slot / 2 ** 20, 1) if first_slot > 0 else "separate allocations"}
     big = arena * 4 >= (64 << 20)                       # a probe is pointless for tiny models
     if big and args.placement != "packed" and torch.cuda.mem_get_info()[0] > (W + 2) * per + (8 << 30):
+        for _ in range(20):                              # the first drains of a process run slower than the rest:
+            step()                                       # none of them goes into a probe
+        b.p3_sync(plan)
         timed_probe = probe(chosen)
         packed = place(per, chosen["views"])
         packed_ms = probe(packed)
@@ -430,7 +479,7 @@ def main():
         "placement": placement,
         "selector_us": {"first_publication": round(sel_first_ns / 1e3, 2), "finished": round(sel_done_ns / 1e3, 2)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args, S),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args, S, cfg["slice_elems"]),
                      "kernel": "p3_drain_kernel", "kernel_avg_ms": round(kern_avg_ms, 4),
                      "kernel_median_ms": round(float(np.median(kern_each)), 4),
                      "kernel_min_ms": round(float(kern_each.min()), 4), "launches": launches,
@@ -443,6 +492,8 @@ def main():
         out["layer_visible_us"] = {"priority": curve_priority, "fifo_policy": curve_fifo}
     if args.overlap:
         out["overlap"] = overlap_study(b, torch, plan, sizes, stream)
+    if args.fixed_cost:
+        out["fixed_cost"] = fixed_cost_study(b, torch)
 
     if not args.no_cpu_baseline:
         import oracle
