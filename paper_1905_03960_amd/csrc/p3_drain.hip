@@ -493,11 +493,13 @@ __device__ __attribute__((noinline)) void complete_layer(FlushCtx a, int layer, 
     const uint32_t round = uni(q) + 1u;
     if (lane_is(lane, 0)) o = __hip_atomic_exchange(&a.layer_req[layer], round, __ATOMIC_RELAXED, P3_AGENT);
     (void)uni(o);                                   // the note has been performed before anyone can acknowledge for it
-    // tell every XCD (lane x tells XCD x); layer 0 is the layer the next forward pass needs first: no delay for it
+    // tell every XCD (lane x tells XCD x); the first layers are what the next forward pass needs first: their
+    // rounds are served without the delay that busy workgroups otherwise leave between two write-backs
     uint32_t h = 0u;
     if (lane < P3_MAX_XCD) {
         h = __hip_atomic_fetch_max(&a.ctl->xcd[lane].req, round, __ATOMIC_RELAXED, P3_AGENT);
-        if (layer == 0) h += __hip_atomic_fetch_max(&a.ctl->xcd[lane].urgent, round, __ATOMIC_RELAXED, P3_AGENT);
+        if (layer < P3_URGENT_LAYERS)
+            h += __hip_atomic_fetch_max(&a.ctl->xcd[lane].urgent, round, __ATOMIC_RELAXED, P3_AGENT);
     }
     (void)uni(h);
     const FlushView f = view_of(load_flush_view(a.ctl, xcd));

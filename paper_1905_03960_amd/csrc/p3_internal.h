@@ -17,7 +17,8 @@
 #define P3_RETIRE_BATCH 4           // tiles of one long run a workgroup finishes before it adds them to the layer's count
 #define P3_LONG_RUN_TILES_PER_WG 8u // a run is long when it gives every workgroup at least this many tiles
 #define P3_PUBLISHED 0x80000000u   // layer_req: the layer's done flag has been written
-#define P3_FLUSH_GAP_TICKS 5000u   // busy workgroups leave 50 us (100 MHz clock) between two write-backs of one L2
+#define P3_FLUSH_GAP_TICKS 5000u   // busy workgroups leave 50 us (100 MHz clock) between two write-backs of one L2 ...
+#define P3_URGENT_LAYERS 8         // ... except for the completion of one of the first layers (the forward pass is waiting)
 #define P3_INLINE_MARKS 256      // marks handed to a SNAPSHOT/TICKED drain with its launch arguments
 
 // Device-side status of a drain (written to pinned host memory at its end).

@@ -160,10 +160,14 @@ def link_cost(gbps, bytes_per_elem=4, per_message_us=0.0):
     return (per_message_us * 1e-6, bytes_per_elem * 8.0 / (gbps * 1e9))
 
 
-def hbm_update_cost(W=8, grad_bytes=4, hbm_TBps=6.53, per_slice_ns=9.0):
+MI355X_DRAIN_TBPS = 6.69      # VGG-19, W=8 fp32: 6.896 GB in 1.031 ms (kernel time; see profiles/)
+
+
+def hbm_update_cost(W=8, grad_bytes=4, hbm_TBps=MI355X_DRAIN_TBPS, per_slice_ns=9.0):
     """(fixed, per_elem) of the update stage when it is the drain kernel of this
-    library: W*grad_bytes + 16 bytes of HBM traffic per parameter at the measured
-    rate, and the selector's time per slice.  Defaults: VGG-19, W=8 fp32 on MI355X."""
+    library: W*grad_bytes + 16 bytes of HBM traffic per parameter at the rate
+    `hbm_TBps` (pass the rate measured for the workload; the default is the one of
+    VGG-19, W=8 fp32 on MI355X), and the selector's time per slice."""
     return (per_slice_ns * 1e-9, (W * grad_bytes + 16) / (hbm_TBps * 1e12))
 
 
@@ -202,12 +206,15 @@ def main(argv=None):
     ap.add_argument("--compute-split", default="uniform", choices=("uniform", "by_params"))
     ap.add_argument("--update", default="mi355x", choices=("mi355x", "link"),
                     help="update stage: this library's measured drain rate, or as slow as the link (a CPU server)")
+    ap.add_argument("--drain-TBps", type=float, default=MI355X_DRAIN_TBPS,
+                    help="HBM rate of the drain kernel for --update mi355x (measured: bench.py, roofline.achieved)")
     ap.add_argument("--slice-elems", type=int, nargs="*", default=[1000, 10000, 50000, 500000, 5000000])
     a = ap.parse_args(argv)
     cfg = sy.config(a.workload)
     layers = cfg["layers"]
     link = link_cost(a.gbps, 4, a.per_message_us)
-    upd = hbm_update_cost(cfg["W"], 2 if cfg["dtype"] == "bf16" else 4) if a.update == "mi355x" else link
+    upd = (hbm_update_cost(cfg["W"], 2 if cfg["dtype"] == "bf16" else 4, a.drain_TBps) if a.update == "mi355x"
+           else link)
     cost = {"push": link, "update": upd, "pull": link}
     bwd = split_compute(layers, a.compute_ms * 1e-3, a.compute_split)
     fwd = split_compute(layers, a.compute_ms * 0.5e-3, a.compute_split)

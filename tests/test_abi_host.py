@@ -177,6 +177,33 @@ def test_bind_argument_checks_come_before_any_gpu_use():
     assert lib.p3_bind(p.handle, 1, odd, 0, 4096, 4096) == b.P3_ERR_ARG     # misaligned gradients
 
 
+def test_arena_stride_hint_and_static_drain_argument_checks():
+    """Host-only parts of the two calls that need no bound plan: the placement hint is a multiple of 2^29
+    gradient elements that holds an arena, and the allocation-free drain refuses bad arguments before it
+    touches the GPU."""
+    lib = b.load()
+    small, big = b.p3_plan([1000, 64], 50000), b.p3_plan([700_000_000], 50000)
+    assert b.p3_suggest_arena_stride(small, b.P3_GRAD_FP32) == 1 << 31
+    assert b.p3_suggest_arena_stride(small, b.P3_GRAD_BF16) == 1 << 30
+    assert b.p3_suggest_arena_stride(big, b.P3_GRAD_FP32) == 1 << 32          # 2.8 GB of weights: two units
+    assert b.p3_suggest_arena_stride(big, b.P3_GRAD_BF16) == 3 << 30
+    assert b.p3_suggest_arena_stride(big, b.P3_GRAD_FP32) >= 4 * b.p3_arena_elems(big)
+    assert lib.p3_suggest_arena_stride(None, 0) == b.P3_ERR_ARG and lib.p3_suggest_arena_stride(small.handle, 5) == b.P3_ERR_ARG
+    ptrs = (C.c_void_p * 1)(4096)
+    marks = (C.c_int32 * 2)(1, 1)
+    args = (0.1, 0.9, 1.0, 0.0)
+    call = lambda plan, W, g, dt, w, m, mk, n, out, res: lib.p3_drain_static(plan, W, g, dt, w, m, *args, mk, n, out, res, None)
+    assert call(None, 1, ptrs, 0, 4096, 4096, marks, 1, 4096, 4096) == b.P3_ERR_ARG
+    assert call(small.handle, 1, ptrs, 0, 4096, 4096, marks, 1, None, 4096) == b.P3_ERR_ARG
+    assert call(small.handle, 1, ptrs, 0, 4096, 4096, None, 1, 4096, 4096) == b.P3_ERR_ARG
+    assert call(small.handle, 1, ptrs, 3, 4096, 4096, marks, 1, 4096, 4096) == b.P3_ERR_ARG
+    assert call(small.handle, 65, ptrs, 0, 4096, 4096, marks, 1, 4096, 4096) == b.P3_ERR_RANGE
+    assert call(small.handle, 1, ptrs, 0, 4100, 4096, marks, 1, 4096, 4096) == b.P3_ERR_ARG     # misaligned weights
+    assert call(small.handle, 1, ptrs, 0, 4096, 4096, marks, 2, 4096, 4096) == b.P3_ERR_ALREADY # layer 1 twice
+    assert call(big.handle, 1, ptrs, 0, 4096, 4096, marks, 1, 4096, 4096) == b.P3_ERR_RANGE     # 14,000 slices
+    assert b.P3_STATIC_MAX_LAYERS == 256 and b.P3_STATIC_MAX_SLICES == 4096
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
