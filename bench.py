@@ -31,8 +31,8 @@ HBM_PEAK_GBPS = 8000.0
 # profiles/p3_drain_kernel_*_hbm_traffic.md (already scaled by what the counters read for a plain copy), valid
 # for the kernel sources whose hash is given, the workload's default slice size and the default launch shape.
 TRAFFIC = {
-    "sources_sha256": "861fd9123427242f48079b38f5717989d091c78750081a12b2eddb1eb7db000b",
-    "bytes_per_launch": {"vgg19": 6902762925, "vgg19_bf16": 6902798111},
+    "sources_sha256": "2ede74125f80fff538cc2f86cba24ee525084b31a4bab3030a73a8625a864e55",
+    "bytes_per_launch": {"vgg19": 6902753390, "vgg19_bf16": 6902716045},
 }
 
 
