@@ -62,72 +62,138 @@ def measured_traffic(args, slice_elems, default_slice_elems):
     return (TRAFFIC["bytes_per_launch"].get(args.workload) or None) if same else None
 
 
-def overlap_study(b, torch, plan, sizes, stream, gemm_rows=2048, reps=5):
-    """The drain beside a producer: one bf16 GEMM (gemm_rows x 4096 x 4096) per layer stands for the layer's
-    backward step on a producer stream, and the layer is marked as that stream's next operation.  Three ways
-    to place the drain, each the best of `reps` iterations (ms from the first enqueue to the last update;
+def stream_beside(torch, other, tries=16):
+    """A new stream whose kernels run while a kernel of `other` is still running: HIP multiplexes streams over a
+    few hardware queues, and two streams that share one are served one after the other (a live drain in front
+    of its producer on such a pair would end by its watchdog).  Candidates are tried until one overlaps."""
+    probe = torch.zeros(256, device="cuda")
+    for _ in range(tries):
+        cand = torch.cuda.Stream()
+        busy, done = torch.cuda.Event(), torch.cuda.Event()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(other):
+            torch.cuda._sleep(60_000_000)
+            busy.record(other)
+        with torch.cuda.stream(cand):
+            probe.add_(1)
+            done.record(cand)
+        done.synchronize()
+        ok = not busy.query()
+        torch.cuda.synchronize()
+        if ok:
+            return cand
+    raise RuntimeError("no stream found that runs beside the drain's")
+
+
+def overlap_study(b, torch, plan, sizes, stream, reps=5):
+    """The drain beside a producer: one bf16 GEMM (rows x 4096 x 4096) per layer stands for the layer's
+    backward step on a producer stream, and the layer is marked as that stream's next operation.  Ways to
+    place the drain, each the best of `reps` iterations (ms from the first enqueue to the last update;
     device time from the selector seeing layer 0 to layer 0 being visible):
       serial        one snapshot drain on a second stream, after an event behind the last mark
       per_layer     a snapshot drain behind every mark (event + wait), so urgent layers go first among
                     whatever has been produced
-      live_reserved one live drain launched before the backward, 64 compute units left to the producer"""
+      live_reserved one live drain launched before the backward, 64 compute units left to the producer
+      live_lean     one live drain of the lean build (256-lane workgroups that share their compute unit)
+                    launched before the backward, nothing reserved
+    for three producers: GEMMs of 2048 rows (the library picks a kernel whose wavefronts take a SIMD's whole
+    register file: nothing fits beside them), of 1536 rows (a kernel that leaves room), and two GEMMs of
+    1536 rows per layer (a backward step computes a data gradient and a weight gradient)."""
     L = len(sizes)
-    producer = torch.cuda.Stream()
-    A = torch.randn(gemm_rows, 4096, device="cuda", dtype=torch.bfloat16)
+    producer = stream_beside(torch, stream)
     B = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
-    C = torch.empty(gemm_rows, 4096, device="cuda", dtype=torch.bfloat16)
     evs = [torch.cuda.Event() for _ in range(L)]
 
-    def backward(mark, drain_each):
-        for l in range(L - 1, -1, -1):
-            with torch.cuda.stream(producer):
-                torch.matmul(A, B, out=C)
-                if mark:
+    def study(rows, per_layer, with_wide_live):
+        A = torch.randn(rows, 4096, device="cuda", dtype=torch.bfloat16)
+        C = torch.empty(rows, 4096, device="cuda", dtype=torch.bfloat16)
+
+        def backward(mark, drain_each):
+            for l in range(L - 1, -1, -1):
+                with torch.cuda.stream(producer):
+                    for _ in range(per_layer):
+                        torch.matmul(A, B, out=C)
+                    if mark:
+                        b.p3_mark_ready_on_stream(plan, l, producer.cuda_stream)
+                    if mark and (drain_each or l == 0):
+                        evs[l].record(producer)
+                        stream.wait_event(evs[l])
+                        b.p3_drain(plan, stream.cuda_stream)
+
+        def live():
+            b.p3_drain(plan, stream.cuda_stream)
+            for l in range(L - 1, -1, -1):
+                with torch.cuda.stream(producer):
+                    for _ in range(per_layer):
+                        torch.matmul(A, B, out=C)
                     b.p3_mark_ready_on_stream(plan, l, producer.cuda_stream)
-                if mark and (drain_each or l == 0):
-                    evs[l].record(producer)
-                    stream.wait_event(evs[l])
-                    b.p3_drain(plan, stream.cuda_stream)
 
-    def timed(fn):
-        best, lat = None, None
+        def timed(fn, n=reps):
+            best, lat = None, None
+            for _ in range(n):
+                b.p3_begin_iter(plan)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                fn()
+                try:
+                    b.p3_sync(plan, 10000)
+                except b.P3Error as e:
+                    torch.cuda.synchronize()
+                    return {"ms": None, "note": f"the producer's kernels did not start beside the resident drain; "
+                                                f"the drain's watchdog ended it ({e})"}
+                torch.cuda.synchronize()
+                t = (time.perf_counter() - t0) * 1e3
+                if best is None or t < best:
+                    best, lat = t, b.p3_layer_latency_ns(plan, 0)[1] / 1e3
+            return {"ms": round(best, 3), "layer0_device_us": round(lat, 1)}
+
+        def drain_alone():
+            b.p3_profile_enable(plan, True)
+            for _ in range(10):
+                b.p3_begin_iter(plan)
+                b.p3_mark_ready_many(plan, list(range(L - 1, -1, -1)))
+                b.p3_drain(plan, stream.cuda_stream)
+            b.p3_sync(plan)
+            ms, n = b.p3_profile_read(plan)
+            b.p3_profile_enable(plan, False)
+            return round(ms / n, 4)
+
+        res = {"producer": f"{L * per_layer} bf16 GEMMs {rows}x4096x4096, {per_layer} per layer, marks on the "
+                           f"producer stream"}
+        for _ in range(2):
+            backward(False, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         for _ in range(reps):
-            b.p3_begin_iter(plan)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            fn()
-            b.p3_sync(plan, 10000)
-            torch.cuda.synchronize()
-            t = (time.perf_counter() - t0) * 1e3
-            if best is None or t < best:
-                best, lat = t, b.p3_layer_latency_ns(plan, 0)[1] / 1e3
-        return {"ms": round(best, 3), "layer0_device_us": round(lat, 1)}
+            backward(False, False)
+        torch.cuda.synchronize()
+        res["backward_alone_ms"] = round((time.perf_counter() - t0) / reps * 1e3, 3)
+        res["drain_alone_ms"] = drain_alone()
+        res["serial"] = timed(lambda: backward(True, False))
+        if with_wide_live:
+            res["per_layer"] = timed(lambda: backward(True, True))
+            b.p3_set_mode(plan, b.P3_MODE_LIVE)
+            b.p3_set_reserved_cus(plan, 64)
+            res["live_reserved"] = timed(live)
+            b.p3_set_reserved_cus(plan, 0)
+            b.p3_set_mode(plan, b.P3_MODE_SNAPSHOT)
+        # the lean build: first alone (snapshot drains), then resident beside the backward pass
+        b.p3_set_launch(plan, b.P3_LAUNCH_LEAN)
+        res["lean_drain_alone_ms"] = drain_alone()
+        b.p3_set_mode(plan, b.P3_MODE_LIVE)
+        b.p3_set_tuning(plan, watchdog_ms=300)       # a producer that cannot start shows after 0.3 s
+        first = timed(live, 1)
+        res["live_lean"] = timed(live) if first["ms"] is not None else first
+        b.p3_set_tuning(plan, watchdog_ms=10000)
+        b.p3_set_mode(plan, b.P3_MODE_SNAPSHOT)
+        b.p3_set_launch(plan, b.P3_LAUNCH_FUSED)
+        if res["live_lean"]["ms"] is not None:
+            res["live_lean"]["of_serial_sum"] = round(res["live_lean"]["ms"] /
+                                                      (res["backward_alone_ms"] + res["drain_alone_ms"]), 3)
+        return res
 
-    res = {"producer": f"{L} bf16 GEMMs {gemm_rows}x4096x4096, one per layer, marks on the producer stream"}
-    for _ in range(2):
-        backward(False, False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        backward(False, False)
-    torch.cuda.synchronize()
-    res["backward_alone_ms"] = round((time.perf_counter() - t0) / reps * 1e3, 3)
-    res["serial"] = timed(lambda: backward(True, False))
-    res["per_layer"] = timed(lambda: backward(True, True))
-    b.p3_set_mode(plan, b.P3_MODE_LIVE)
-    b.p3_set_reserved_cus(plan, 64)
-
-    def live():
-        b.p3_drain(plan, stream.cuda_stream)
-        for l in range(L - 1, -1, -1):
-            with torch.cuda.stream(producer):
-                torch.matmul(A, B, out=C)
-                b.p3_mark_ready_on_stream(plan, l, producer.cuda_stream)
-
-    res["live_reserved"] = timed(live)
-    b.p3_set_mode(plan, b.P3_MODE_SNAPSHOT)
-    b.p3_set_reserved_cus(plan, 0)
-    return res
+    return {"gemm_rows_2048": study(2048, 1, True), "gemm_rows_1536": study(1536, 1, False),
+            "gemm_rows_1536_two_per_layer": study(1536, 2, False)}
 
 
 def fixed_cost_study(b, torch, W=8, sizes_m=(24, 48, 96, 144), reps=12):

@@ -198,11 +198,23 @@ int p3_set_tuning(p3_plan_t* plan, int32_t tile_elems, int32_t wgs_per_cu,
  * Takes effect at the next p3_begin_iter.  Errors: ARG. */
 int p3_set_reserved_cus(p3_plan_t* plan, int32_t n_cus);
 
-/* How a SNAPSHOT or TICKED drain is put on the stream.  1 (default): one
- * persistent launch in which workgroup 0 selects while the others already work
- * (what LIVE always uses).  0: two launches, the selector (one workgroup) and
- * then the workers over the finished work queue; no workgroup waits for
- * another.  Taken by the next p3_drain.  Errors: ARG. */
+/* How a drain is put on the stream.  1 (default): one persistent launch in
+ * which workgroup 0 selects while the others already work (what LIVE always
+ * uses); a workgroup owns its compute unit.  0: two launches for a SNAPSHOT or
+ * TICKED drain, the selector (one workgroup) and then the workers over the
+ * finished work queue; no workgroup waits for another.  2: the persistent
+ * launch with workgroups of 256 lanes and a quarter of the register file, which
+ * leave room on every compute unit for workgroups of other kernels: a live
+ * drain launched before a backward pass on another stream then runs beside it
+ * instead of in front of it (Sec. 4: synchronisation overlapped with the
+ * backward pass).  Alone it streams at two thirds of the default's rate; a
+ * kernel whose wavefronts take a SIMD's whole register file still cannot start
+ * beside it (p3_set_reserved_cus is for those).  Results are the same bits in
+ * all three.  0 and 1 are taken by the next p3_drain, a change to or from 2 by
+ * the next p3_begin_iter (the default tile size differs).  Errors: ARG. */
+#define P3_LAUNCH_SPLIT 0
+#define P3_LAUNCH_FUSED 1
+#define P3_LAUNCH_LEAN 2
 int p3_set_launch(p3_plan_t* plan, int32_t persistent);
 
 /* ---- one iteration ----
@@ -241,8 +253,15 @@ int p3_mark_ready_many(p3_plan_t* plan, const int32_t* layers, int32_t n);
  * with nothing more claimed and p3_sync reports INCOMPLETE).  The gradients must
  * be written by operations that precede the mark on that stream.  A drain that
  * occupies every compute unit while it waits keeps the producer's kernels from
- * starting: see p3_set_reserved_cus.  host_ns of p3_layer_latency_ns counts
- * from this call, not from the moment the stream reaches the mark.
+ * starting: see p3_set_reserved_cus and p3_set_launch(plan, P3_LAUNCH_LEAN).
+ * The same holds, whatever the launch, when the drain's stream and the
+ * producer's share a hardware queue: HIP serves its streams through a few of
+ * them (four by default), two streams on one queue run one after the other,
+ * and which streams share one is not documented -- check that a kernel of one
+ * stream starts while a kernel of the other is running before relying on it
+ * (a drain that waits in vain ends by its time limit).  host_ns of
+ * p3_layer_latency_ns counts from this call, not from the moment the stream
+ * reaches the mark.
  * Errors: as p3_mark_ready, DEVICE. */
 int p3_mark_ready_on_stream(p3_plan_t* plan, int32_t layer, void* producer_stream);
 

@@ -24,6 +24,7 @@ P3_ERR_NOMEM, P3_ERR_DEVICE, P3_ERR_TIMEOUT, P3_ERR_INCOMPLETE = -5, -6, -7, -8
 P3_GRAD_FP32, P3_GRAD_BF16 = 0, 1
 P3_MODE_SNAPSHOT, P3_MODE_LIVE, P3_MODE_TICKED = 0, 1, 2
 P3_POLICY_PRIORITY, P3_POLICY_FIFO = 0, 1
+P3_LAUNCH_SPLIT, P3_LAUNCH_FUSED, P3_LAUNCH_LEAN = 0, 1, 2
 P3_MAX_WORKERS = 64
 P3_STATIC_MAX_LAYERS, P3_STATIC_MAX_SLICES = 256, 4096
 
@@ -260,7 +261,7 @@ def p3_set_reserved_cus(plan, n_cus):
 
 
 def p3_set_launch(plan, persistent):
-    _check(load().p3_set_launch(_h(plan), 1 if persistent else 0), "p3_set_launch")
+    _check(load().p3_set_launch(_h(plan), int(persistent)), "p3_set_launch")
 
 
 def p3_begin_iter(plan):

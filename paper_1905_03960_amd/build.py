@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libp3.so")
-SOURCES = ["p3_runtime.hip", "p3_drain.hip"]
+SOURCES = ["p3_runtime.hip", "p3_drain.hip", "p3_drain_lean.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",

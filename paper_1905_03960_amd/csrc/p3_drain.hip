@@ -31,6 +31,31 @@
 
 #pragma clang fp contract(off)
 
+// Build parameters (p3_drain_lean.hip sets them and includes this file): a namespace for everything below, so
+// that two builds can live in one library; the names of the two entry points; attributes of the kernels; how
+// many loads a lane issues ahead of the one it is folding in.
+#ifdef P3_NS
+#define P3_NS_BEGIN namespace P3_NS {
+#define P3_NS_END }
+#define P3_NS_Q P3_NS::
+#else
+#define P3_NS_BEGIN
+#define P3_NS_END
+#define P3_NS_Q
+#endif
+#ifndef P3_LAUNCH_SYM
+#define P3_LAUNCH_SYM p3_launch_drain
+#define P3_OCCUPANCY_SYM p3_drain_occupancy
+#endif
+#ifndef P3_KERNEL_ATTR
+#define P3_KERNEL_ATTR
+#endif
+#ifndef P3_LOADS_AHEAD
+#define P3_LOADS_AHEAD 1
+#endif
+
+P3_NS_BEGIN
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -213,7 +238,31 @@ __device__ __forceinline__ void do_quads_f32(const P3GradPtrs& gp, int W, const 
                                              __amdgpu_buffer_rsrc_t rw, __amdgpu_buffer_rsrc_t rm,
                                              const H& h) {
     f32x4 s[NV], wv[NV], mv[NV];
-    if constexpr (WT > 0) {
+    if constexpr (WT > 0 && P3_LOADS_AHEAD > 1) {
+        // the same sequence with P3_LOADS_AHEAD loads issued ahead of the one being folded in: a workgroup of
+        // few lanes needs that many in flight to fill what its compute unit can keep outstanding
+        constexpr int NL = (WT + 2) * NV;
+        constexpr int D = P3_LOADS_AHEAD < NL ? P3_LOADS_AHEAD : NL - 1;
+        f32x4 r[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+#pragma unroll
+            for (int k = (i == 0 ? 0 : i + D); k <= i + D && k < NL; ++k) {
+                const int st = k / NV;
+                const int64_t at = q + (k % NV) * P3_BLOCK;
+                r[k] = st < WT    ? __builtin_nontemporal_load(static_cast<const f32x4*>(gp.p[st]) + at)
+                       : st == WT ? __builtin_nontemporal_load(w4 + at)
+                                  : __builtin_nontemporal_load(m4 + at);
+            }
+            f32x4 cur = r[i];
+            pin(cur);
+            const int st = i / NV, u = i % NV;
+            if (st == 0) s[u] = cur;
+            else if (st < WT) s[u] = s[u] + cur;
+            else if (st == WT) wv[u] = cur;
+            else mv[u] = cur;
+        }
+    } else if constexpr (WT > 0) {
         // sequence position i: stream i / NV (gradient copies, then weights, then momentum), vector i % NV
         constexpr int NL = (WT + 2) * NV;
         f32x4 nxt = __builtin_nontemporal_load(static_cast<const f32x4*>(gp.p[0]) + q);
@@ -1752,7 +1801,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
 
 // One launch: selector in workgroup 0, every workgroup a worker (LIVE needs this).
 template <int WT, bool BF16, bool WD>
-__global__ void __launch_bounds__(P3_BLOCK) p3_drain_kernel(const P3DrainArgs a, const P3GradPtrs gp) {
+__global__ void __launch_bounds__(P3_BLOCK) P3_KERNEL_ATTR p3_drain_kernel(const P3DrainArgs a, const P3GradPtrs gp) {
     __shared__ SelectorLds lds;
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
@@ -1762,14 +1811,14 @@ __global__ void __launch_bounds__(P3_BLOCK) p3_drain_kernel(const P3DrainArgs a,
 }
 
 // Two launches on one stream: the selector alone (one workgroup) ...
-__global__ void __launch_bounds__(P3_BLOCK) p3_select_kernel(const P3DrainArgs a) {
+__global__ void __launch_bounds__(P3_BLOCK) P3_KERNEL_ATTR p3_select_kernel(const P3DrainArgs a) {
     __shared__ SelectorLds lds;
     run_selector(a, lds);
 }
 
 // ... then the workers over the finished queue; no workgroup ever waits for another.
 template <int WT, bool BF16, bool WD>
-__global__ void __launch_bounds__(P3_BLOCK) p3_work_kernel(const P3DrainArgs a, const P3GradPtrs gp) {
+__global__ void __launch_bounds__(P3_BLOCK) P3_KERNEL_ATTR p3_work_kernel(const P3DrainArgs a, const P3GradPtrs gp) {
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
     if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), true);
@@ -1811,12 +1860,14 @@ static p3_kernel_t pick(int W, int grad_dtype, int with_wd, int persistent) {
     return with_wd ? pick2<false, true>(W, persistent) : pick2<false, false>(W, persistent);
 }
 
-extern "C" int p3_launch_drain(const P3DrainArgs* args, const P3GradPtrs* grads, int grad_dtype,
-                               int persistent, unsigned grid, void* stream) {
+P3_NS_END
+
+extern "C" int P3_LAUNCH_SYM(const P3DrainArgs* args, const P3GradPtrs* grads, int grad_dtype,
+                             int persistent, unsigned grid, void* stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    p3_kernel_t k = pick(args->W, grad_dtype, args->wd != 0.0f ? 1 : 0, persistent);
+    P3_NS_Q p3_kernel_t k = P3_NS_Q pick(args->W, grad_dtype, args->wd != 0.0f ? 1 : 0, persistent);
     if (!persistent) {
-        hipLaunchKernelGGL(p3_select_kernel, dim3(1), dim3(P3_BLOCK), 0, st, *args);
+        hipLaunchKernelGGL(P3_NS_Q p3_select_kernel, dim3(1), dim3(P3_BLOCK), 0, st, *args);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return static_cast<int>(e);
     }
@@ -1824,8 +1875,8 @@ extern "C" int p3_launch_drain(const P3DrainArgs* args, const P3GradPtrs* grads,
     return static_cast<int>(hipGetLastError());
 }
 
-extern "C" int p3_drain_occupancy(int W, int grad_dtype, int persistent, int* blocks_per_cu) {
-    p3_kernel_t k = pick(W, grad_dtype, 1, persistent);   // the weight-decay variant uses no fewer registers
+extern "C" int P3_OCCUPANCY_SYM(int W, int grad_dtype, int persistent, int* blocks_per_cu) {
+    P3_NS_Q p3_kernel_t k = P3_NS_Q pick(W, grad_dtype, 1, persistent);   // the weight-decay variant uses no fewer registers
     return static_cast<int>(hipOccupancyMaxActiveBlocksPerMultiprocessor(
         blocks_per_cu, reinterpret_cast<const void*>(k), P3_BLOCK, 0));
 }

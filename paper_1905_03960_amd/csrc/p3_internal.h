@@ -7,8 +7,16 @@
 
 #include "p3_tiles.h"
 
+// The drain kernel is built twice from one source.  The wide build is the default: one workgroup owns a
+// compute unit.  The lean build (p3_drain_lean.hip) has workgroups of four wavefronts with at most 128
+// registers a lane, a quarter of each SIMD's register file, so that workgroups of other kernels -- a backward
+// pass on another stream -- find room on the same compute unit while the drain is resident.
+#ifndef P3_BLOCK
 #define P3_BLOCK 832            // threads per workgroup = 13 wavefronts of 64, one workgroup per CU (measured optimum
                                 // with the arenas well placed: 704 lanes 1.067 ms, 768 1.032, 832 1.020, 896 1.035, 960 1.045)
+#endif
+#define P3_BLOCK_LEAN 256       // threads per workgroup of the lean build
+#define P3_TILE_LEAN 4096       // its default tile: four steps of the workgroup
 #define P3_WAVES (P3_BLOCK / 64)
 #define P3_BATCH_MAX P3_BLOCK   // slices the selector claims per publication step (one per selector thread)
 #define P3_NONE 0xffffffffu     // "final queue length not known yet"
@@ -44,8 +52,12 @@ struct P3LayerDev {
     int64_t elems;   // parameters of the layer
 };
 
+#ifndef P3_RUN_CACHE
 #define P3_RUN_CACHE 512    // run records a workgroup keeps in LDS (a ring; power of two)
+#endif
+#ifndef P3_LDS_BM_WORDS
 #define P3_LDS_BM_WORDS 4096   // the selector keeps the ready bitmap in LDS when it has at most this many words (262,144 slices)
+#endif
 #define P3_LDS_LAYERS 2048     // ... and the layer states when there are at most this many layers
 
 // Per-XCD part of the write-back rounds.  Every leader reads the first 16 bytes of
@@ -168,6 +180,10 @@ int p3_launch_drain(const P3DrainArgs* args, const P3GradPtrs* grads, int grad_d
                     int persistent, unsigned grid, void* stream);
 // Resident workgroups per compute unit of the kernel that (W, dtype, persistent) selects.
 int p3_drain_occupancy(int W, int grad_dtype, int persistent, int* blocks_per_cu);
+// The same two for the lean build (defined in p3_drain_lean.hip).
+int p3_launch_drain_lean(const P3DrainArgs* args, const P3GradPtrs* grads, int grad_dtype,
+                         int persistent, unsigned grid, void* stream);
+int p3_drain_occupancy_lean(int W, int grad_dtype, int persistent, int* blocks_per_cu);
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,7 @@ struct p3_plan_s : P3PlanTables {
     int32_t lookahead = 0;             // 0: derive from the grid
     int32_t watchdog_ms = 10000;
     int32_t persistent = 1;            // SNAPSHOT/TICKED: one fused launch (1) or selector + workers (0)
+    int32_t lean = 0, next_lean = -1;  // 1: the build with small workgroups that share their compute unit
     // set by p3_set_mode / p3_set_tuning, applied by the next p3_begin_iter
     bool pending_mode = false, pending_tuning = false;
     int32_t next_mode = P3_MODE_SNAPSHOT;
@@ -328,7 +329,7 @@ int p3_slice_info(const p3_plan_t* p, int32_t g, int32_t* layer, int64_t* offset
 // consecutive parameters (more steps per tile were measured to cost bandwidth).
 static int32_t tile_of_plan(const p3_plan_s* p) {
     if (p->tile_elems) return p->tile_elems;
-    return P3_BLOCK * 4;
+    return p->lean ? P3_TILE_LEAN : P3_BLOCK * 4;
 }
 
 static int alloc_queue(p3_plan_s* p) {
@@ -345,7 +346,9 @@ static int alloc_queue(p3_plan_s* p) {
 
 static int size_grid(p3_plan_s* p) {
     int occ = 0;
-    if (HIPC(static_cast<hipError_t>(p3_drain_occupancy(p->W, p->dtype, 1, &occ))) != hipSuccess || occ < 1)
+    if (HIPC(static_cast<hipError_t>((p->lean ? p3_drain_occupancy_lean : p3_drain_occupancy)(p->W, p->dtype, 1, &occ))) !=
+            hipSuccess ||
+        occ < 1)
         return P3_ERR_DEVICE;
     int per_cu = p->wgs_per_cu < occ ? p->wgs_per_cu : occ;   // never more than can be co-resident
     if (per_cu < 1) per_cu = 1;
@@ -536,8 +539,11 @@ int p3_set_reserved_cus(p3_plan_t* p, int32_t n_cus) {
 
 int p3_set_launch(p3_plan_t* p, int32_t persistent) {
     if (!p) return P3_ERR_ARG;
-    if (persistent != 0 && persistent != 1) return P3_ERR_ARG;
-    p->persistent = persistent;
+    if (persistent < 0 || persistent > 2) return P3_ERR_ARG;
+    p->persistent = persistent != 0 ? 1 : 0;
+    // the lean build has its own tile size and grid: like them, it changes at an iteration boundary
+    p->next_lean = persistent == 2 ? 1 : 0;
+    p->pending_tuning = true;
     return P3_OK;
 }
 
@@ -561,6 +567,12 @@ static int apply_pending(p3_plan_s* p) {
     if (p->pending_tuning) {
         if (p->next_wgs_per_cu) p->wgs_per_cu = p->next_wgs_per_cu;
         if (p->next_reserved_cus >= 0) p->reserved_cus = p->next_reserved_cus;
+        if (p->next_lean >= 0 && p->next_lean != p->lean) {
+            p->lean = p->next_lean;
+            if (!p->tile_elems)
+                if (int rc = alloc_queue(p)) return rc;      // the default tile differs between the builds
+        }
+        p->next_lean = -1;
         if (p->next_tile_elems && p->next_tile_elems != p->tile_elems) {
             const int32_t old = p->tile_elems;
             p->tile_elems = p->next_tile_elems;
@@ -796,7 +808,8 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
         pp = &p->prof_pool[p->prof_used];
         if (HIPC(hipEventRecord(pp->start, st)) != hipSuccess) return P3_ERR_DEVICE;
     }
-    if (HIPC(static_cast<hipError_t>(p3_launch_drain(&a, &p->grads, p->dtype, (p->mode == P3_MODE_LIVE || p->persistent) ? 1 : 0, p->grid, st))) != hipSuccess)
+    const auto launch = p->lean ? p3_launch_drain_lean : p3_launch_drain;
+    if (HIPC(static_cast<hipError_t>(launch(&a, &p->grads, p->dtype, (p->mode == P3_MODE_LIVE || p->persistent) ? 1 : 0, p->grid, st))) != hipSuccess)
         return P3_ERR_DEVICE;
     if (pp) {
         if (HIPC(hipEventRecord(pp->stop, st)) != hipSuccess) return P3_ERR_DEVICE;

@@ -11,6 +11,32 @@ PAD_W = np.float32(12345.0)       # sentinel in weight/momentum padding: must su
 PAD_G = np.float32(np.nan)        # gradient padding: must never be read into a result
 
 
+def stream_beside(*others, tries=16):
+    """A new stream whose kernels run while kernels of `others` are still running.  HIP multiplexes its streams
+    over a few hardware queues (four by default), and two streams that share a queue are served one after the
+    other: a live drain launched in front of its producer on such a pair would wait for marks that cannot be
+    made until it has ended.  Which streams share a queue is not documented, so candidates are tried."""
+    probe = torch.zeros(256, device="cuda")
+    for _ in range(tries):
+        cand = torch.cuda.Stream()
+        ok = True
+        for other in others:
+            busy, done = torch.cuda.Event(), torch.cuda.Event()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(other):
+                torch.cuda._sleep(60_000_000)            # tens of milliseconds
+                busy.record(other)
+            with torch.cuda.stream(cand):
+                probe.add_(1)
+                done.record(cand)
+            done.synchronize()
+            ok = ok and not busy.query()                # the candidate's kernel finished while the other still spins
+            torch.cuda.synchronize()
+        if ok:
+            return cand
+    raise RuntimeError("no stream found that runs beside the given ones")
+
+
 def bits(a):
     return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
 

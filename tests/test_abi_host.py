@@ -151,6 +151,9 @@ def test_calls_before_bind_are_state_errors_and_indices_are_checked():
     assert lib.p3_set_tuning(h, 4096, 2, 0, 0) == b.P3_OK
     assert lib.p3_set_tuning(h, 0, 17, 0, 0) == b.P3_ERR_ARG
     assert lib.p3_set_reserved_cus(h, -1) == b.P3_ERR_ARG and lib.p3_set_reserved_cus(h, 32) == b.P3_OK
+    assert lib.p3_set_launch(h, 3) == b.P3_ERR_ARG and lib.p3_set_launch(h, -1) == b.P3_ERR_ARG
+    for kind in (b.P3_LAUNCH_SPLIT, b.P3_LAUNCH_LEAN, b.P3_LAUNCH_FUSED):
+        assert lib.p3_set_launch(h, kind) == b.P3_OK
     assert lib.p3_mark_ready_on_stream(h, 0, None) == b.P3_ERR_STATE        # not bound, no iteration
     assert lib.p3_mark_ready_on_stream(None, 0, None) == b.P3_ERR_ARG
     assert lib.p3_layer_timeline_ns(h, 0, None, None) == b.P3_ERR_STATE and lib.p3_layer_timeline_ns(None, 0, None, None) == b.P3_ERR_ARG

@@ -14,7 +14,7 @@ from oracle import OraclePlan
 from paper_1905_03960_amd import binding as b
 from paper_1905_03960_amd import synthetic as sy
 
-from p3_case import DeviceCase, assert_same_bits, bits
+from p3_case import DeviceCase, assert_same_bits, bits, stream_beside
 
 pytestmark = pytest.mark.gpu
 
@@ -403,7 +403,7 @@ def test_live_layer_zero_visible_while_drain_still_runs():
     b.p3_set_mode(case.plan, b.P3_MODE_LIVE)
     rw, rm = w0.copy(), m0.copy()
     oracle.sgd_whole(grads, rw, rm, 0.1, 0.9)
-    side = torch.cuda.Stream()
+    side = stream_beside(case.stream)
     host = torch.empty(sizes[0], dtype=torch.float32).pin_memory()
     b.p3_begin_iter(case.plan)
     b.p3_drain(case.plan, case.stream.cuda_stream)
@@ -491,7 +491,7 @@ def test_marks_that_follow_the_gradient_writes_on_a_producer_stream(mode):
     if mode == "live":
         b.p3_set_mode(case.plan, b.P3_MODE_LIVE)
     staged = [t.clone() for t in case.g]                      # the real gradients, kept aside
-    producer = torch.cuda.Stream()
+    producer = stream_beside(case.stream)
     o = OraclePlan(sizes, 4096)
     rw, rm = w0.copy(), m0.copy()
     for it in range(3):
@@ -526,17 +526,18 @@ def test_snapshot_drain_gives_up_on_a_stream_mark_that_comes_too_late():
     grads, w0, m0 = draw(862, sum(sizes), 2)
     case = DeviceCase(sizes, 1024, grads, w0, m0, watchdog_ms=200)
     o = OraclePlan(sizes, 1024)
-    producer = torch.cuda.Stream()
+    producer = stream_beside(case.stream)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda._sleep(200_000_000)                             # the spin counts shader clocks: let them ramp up first
     e0.record()
-    torch.cuda._sleep(10_000_000)
+    torch.cuda._sleep(50_000_000)
     e1.record()
     torch.cuda.synchronize()
-    hold = int(800.0 * 10_000_000 / e0.elapsed_time(e1))       # spin cycles for about 0.8 s
+    hold = int(1000.0 * 50_000_000 / e0.elapsed_time(e1))      # spin cycles for about a second
     b.p3_begin_iter(case.plan)
     b.p3_mark_ready(case.plan, 2)
     with torch.cuda.stream(producer):
-        torch.cuda._sleep(hold)                               # a bounded hold-up, four times the watchdog
+        torch.cuda._sleep(hold)                               # a bounded hold-up, five times the watchdog
         b.p3_mark_ready_on_stream(case.plan, 0, producer.cuda_stream)
     b.p3_drain(case.plan, case.stream.cuda_stream)
     with pytest.raises(b.P3Error) as ei:
@@ -564,7 +565,8 @@ def test_consumer_stream_waits_on_the_device_for_the_layers_it_needs():
     case = DeviceCase(sizes, 4096, grads, w0, m0, watchdog_ms=5000)
     b.p3_set_reserved_cus(case.plan, 32)                      # room for the consumer's copy kernels beside the drain
     b.p3_set_mode(case.plan, b.P3_MODE_LIVE)
-    producer, consumer = torch.cuda.Stream(), torch.cuda.Stream()
+    producer = stream_beside(case.stream)
+    consumer = stream_beside(case.stream, producer)
     rw, rm = w0.copy(), m0.copy()
     for it in range(2):
         b.p3_begin_iter(case.plan)
@@ -605,7 +607,7 @@ def test_stream_marks_mix_with_host_marks_and_keep_mark_order():
     grads, w0, m0 = draw(861, sum(sizes), 2)
     case = DeviceCase(sizes, 1000, grads, w0, m0, watchdog_ms=5000)
     b.p3_set_reserved_cus(case.plan, 16)
-    producer = torch.cuda.Stream()
+    producer = stream_beside(case.stream)
     o = OraclePlan(sizes, 1000)
     rw, rm = w0.copy(), m0.copy()
     b.p3_begin_iter(case.plan)
