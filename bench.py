@@ -31,8 +31,8 @@ HBM_PEAK_GBPS = 8000.0
 # profiles/p3_drain_kernel_*_hbm_traffic.md (already scaled by what the counters read for a plain copy), valid
 # for the kernel sources whose hash is given, the workload's default slice size and the default launch shape.
 TRAFFIC = {
-    "sources_sha256": "2ede74125f80fff538cc2f86cba24ee525084b31a4bab3030a73a8625a864e55",
-    "bytes_per_launch": {"vgg19": 6902770096, "vgg19_bf16": 6902743653},
+    "sources_sha256": "dd03bbbf45b828f5fa9894f8fe1e7806d23e1d076e659e8efc296e7de103ba95",
+    "bytes_per_launch": {"vgg19": 6902751399, "vgg19_bf16": 6902750087},
 }
 
 
