@@ -251,7 +251,8 @@ def parse():
     ap.add_argument("--tile-elems", type=int, default=0)
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--reserved-cus", type=int, default=0, help="compute units the drain leaves to other streams")
-    ap.add_argument("--persistent", type=int, default=-1, help="1: one fused launch per drain, 0: selector + workers")
+    ap.add_argument("--persistent", type=int, default=-1, help="1: one fused launch per drain, 0: selector + workers, 2: the lean build (256-lane workgroups that "
+                         "share their compute unit)")
     ap.add_argument("--placement", default="suggested", choices=["suggested", "packed", "separate", "search", "best"],
                     help="where the arenas lie: at the distance p3_suggest_arena_stride gives (default), back to back, "
                          "in separate allocations; 'search' also probes other distances and reports them (the timed "
