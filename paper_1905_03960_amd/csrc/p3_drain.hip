@@ -54,6 +54,9 @@
 #define P3_LOADS_AHEAD 1
 #endif
 
+static_assert(P3_INLINE_RUNS <= P3_RUN_CACHE, "the runs handed over with the launch go into the ring");
+static_assert(sizeof(P3DrainArgs) + sizeof(P3GradPtrs) <= 4096, "the launch arguments of a kernel are limited to 4 KB");
+
 P3_NS_BEGIN
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -845,6 +848,16 @@ __device__ __forceinline__ int take_fifo(const P3DrainArgs& a, uint8_t* ls, Sele
     return nb;
 }
 
+// Does run r of the first selection step (start rs, length rl, layer) differ from what the host handed the
+// workers with the launch?  (Thread r asks; the step must have at least as many runs as were handed over.)
+__device__ __forceinline__ bool first_run_differs(const P3DrainArgs& a, int r, int nruns, long long rs, long long rl,
+                                                  int layer) {
+    if (r >= a.n_first) return false;
+    if (r >= nruns) return true;
+    const P3FirstRun f = a.first_runs[r];
+    return f.start != rs || static_cast<long long>(f.len) != rl || f.layer != layer;
+}
+
 __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: whole wavefronts branch on it
@@ -872,8 +885,12 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
         for (int i = tid; i < a.n_words; i += P3_BLOCK) bm[i] = 0ull;
         for (int i = tid; i < a.L; i += P3_BLOCK) {
             ls[i] = P3L_IDLE;
-            __hip_atomic_store(&a.layer_done[i], 0u, __ATOMIC_RELAXED, P3_AGENT);
-            __hip_atomic_store(&a.layer_req[i], 0u, __ATOMIC_RELAXED, P3_AGENT);
+            // (the counts of THIS iteration were cleared by the first drain of the iteration before; what is
+            // cleared here is the set the next iteration will count in)
+            if (a.layer_done_next != nullptr) {
+                __hip_atomic_store(&a.layer_done_next[i], 0ull, __ATOMIC_RELAXED, P3_AGENT);
+                __hip_atomic_store(&a.layer_req_next[i], 0u, __ATOMIC_RELAXED, P3_AGENT);
+            }
         }
         if (lane_is(tid, 0)) {
             ctl->claimed = 0u;
@@ -897,7 +914,7 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
         const int32_t l = a.inline_marks[tid];
         if (l >= 0 && l < a.L) pre_mine = a.layers[l];
     }
-    wait_vm_done();                     // the cleared counts are in the L2 before anybody can add to them
+    wait_vm_done();                     // the table entries asked for above are here
     if (pre_ok && tid < a.n_inline) lds.pre[tid] = pre_mine;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
@@ -1048,8 +1065,8 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             }
             // a short first step gets the workers going; later steps amortise the publication
             // (as many slices as give every workgroup two tiles, at least what one wavefront groups on its own)
-            int first_cap = (2 * static_cast<int>(a.n_blocks) + a.tiles_per_full_slice - 1) / a.tiles_per_full_slice;
-            first_cap = first_cap < 64 ? 64 : (first_cap > 256 ? 256 : first_cap);
+            // (a full step when the workers have been handed its leading runs with the launch: nobody waits for it)
+            const int first_cap = a.n_first > 0 ? P3_BATCH_MAX : p3_first_step_slices(a.n_blocks, a.tiles_per_full_slice);
             const int batch_cap = st.pub_runs == 0u ? first_cap : P3_BATCH_MAX;
             // every mode: the host may ask the drain to stop, and no drain outlives its watchdog
             // (a read over the host link: every round in LIVE mode, where the drain waits on the
@@ -1209,7 +1226,10 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
                 }
                 const int c_incl = wave_incl_scan(c, lane);
                 const int tb = __shfl(c_incl, 63, 64);
-                const bool fits = st.pub_runs + static_cast<uint32_t>(nruns) <= a.run_cap;
+                bool fits = st.pub_runs + static_cast<uint32_t>(nruns) <= a.run_cap;
+                if (st.pub_runs == 0u && a.n_first > 0 &&
+                    __ballot(first_run_differs(a, lane, nruns, rs, rl, rlayer)) != 0ull)
+                    fits = false;                      // the workers were handed something else: stop
                 if (fits && lane < nruns) {
                     const uint32_t t0 = st.pub_tiles + static_cast<uint32_t>(c_incl - c);
                     unsigned long long* q =
@@ -1309,7 +1329,11 @@ __device__ void run_selector(const P3DrainArgs& a, SelectorLds& lds) {
             if (v < wave) t_before += wc;
             tb += wc;
         }
-        const bool fits = runs_at + static_cast<uint32_t>(nruns) <= a.run_cap;
+        if (runs_at == 0u && a.n_first > 0 &&
+            first_run_differs(a, tid, nruns, rs, rl, tid < nruns ? lds.run_layer[tid] : 0))
+            lds.overflow = 1;                          // the workers were handed something else: stop
+        __syncthreads();
+        const bool fits = runs_at + static_cast<uint32_t>(nruns) <= a.run_cap && uni(static_cast<uint32_t>(lds.overflow)) == 0u;
         if (fits && tid < nruns) {
             const uint32_t t0 = tiles_at + static_cast<uint32_t>(t_before + c_incl - c);
             unsigned long long* q = reinterpret_cast<unsigned long long*>(&a.runq[runs_at + static_cast<uint32_t>(tid)]);
@@ -1665,6 +1689,40 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
 
     // The first round is a DRAIN round with nothing to drain: it finds the tile of the first number.
     if (wave == 0) {
+        if (WAIT && a.n_first > 0) {
+            // the leading runs of the first selection step came with the launch: they go into the ring as if
+            // they had been read from the queue (their tile numbers follow from their order), and the
+            // workgroup starts on them without waiting for the selector
+            // (the host has checked them against the arena; a check here, cheap as it is, was measured to cost
+            // the bf16 kernel 2 % -- scalar registers spilled in the loop below)
+            int t_before = 0;
+            for (int base = 0; base < a.n_first; base += 64) {
+                const int r = base + lane;
+                P3FirstRun fr;
+                fr.start = 0;
+                fr.len = 1u;
+                fr.layer = 0;
+                int c = 0;
+                if (r < a.n_first) {
+                    fr = a.first_runs[r];
+                    c = static_cast<int>(p3_run_cells(fr.start, static_cast<int64_t>(fr.len), a.tile_elems));
+                }
+                const int c_incl = wave_incl_scan(c, lane);
+                if (r < a.n_first) {
+                    P3Run e;
+                    e.start = fr.start;
+                    e.len = static_cast<int64_t>(fr.len);
+                    e.grid_off = static_cast<int32_t>(fr.start % a.tile_elems);
+                    e.layer = fr.layer;
+                    e.tile0 = static_cast<uint32_t>(t_before + c_incl - c);
+                    e.tile_end = static_cast<uint32_t>(t_before + c_incl);
+                    s_runs[r] = e;
+                }
+                t_before += __shfl(c_incl, 63, 64);
+            }
+            r_have = static_cast<uint32_t>(a.n_first);
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");      // the ring is read by other lanes
+        }
         k_wait = uni(take_ticket(ctl, lane));
         P3TileDesc d0;
         d0.start = 0;

@@ -28,12 +28,20 @@
 #define P3_FLUSH_GAP_TICKS 5000u   // busy workgroups leave 50 us (100 MHz clock) between two write-backs of one L2 ...
 #define P3_URGENT_LAYERS 8         // ... except for the completion of one of the first layers (the forward pass is waiting)
 #define P3_INLINE_MARKS 256      // marks handed to a SNAPSHOT/TICKED drain with its launch arguments
+#define P3_INLINE_RUNS 128       // runs of the first selection step handed to a SNAPSHOT drain with its launch arguments
 
 // Device-side status of a drain (written to pinned host memory at its end).
 enum { P3D_OK = 0, P3D_WATCHDOG = 1, P3D_ABORTED = 2, P3D_OVERFLOW = 3 };
 
 // layer_state values (device)
 enum { P3L_IDLE = 0, P3L_PENDING = 1, P3L_RELEASED = 2 };
+
+// A run of the first selection step as the host hands it over: its tile numbers follow from the order.
+struct P3FirstRun {
+    int64_t start;
+    uint32_t len;
+    int32_t layer;
+};
 
 // One slice: a contiguous run of one layer (Sec. 4.2).  start is an element
 // offset into every arena.  32 bytes, so the selector needs one load per slice.
@@ -132,6 +140,11 @@ struct P3DrainArgs {
     int32_t* epoch;               // marks observed at each claim
     unsigned long long* layer_done;   // elements retired per layer this iteration
     uint32_t* layer_req;          // per layer: 0, or the write-back round its completion asked for (| P3_PUBLISHED)
+    // The two arrays above exist twice and iterations alternate between the sets: the first drain of an
+    // iteration clears the set the NEXT iteration will use (nobody else touches it meanwhile), so the set in
+    // use is clean before the launch and a worker may count a tile as early as it likes.  NULL: nothing to clear.
+    unsigned long long* layer_done_next;
+    uint32_t* layer_req_next;
     int32_t* fifo;                // first-come-first-served policy: layers in the order they became ready
     uint64_t* t_seen_dev;         // per layer: device clock when the selector saw it ready
     P3Ctl* ctl;
@@ -169,6 +182,14 @@ struct P3DrainArgs {
     // (else n_inline = 0 and the kernel reads the pinned mark log over the host link)
     int32_t n_inline;
     int32_t inline_marks[P3_INLINE_MARKS];
+    // The first drain of an iteration in SNAPSHOT mode under the priority rule: what the selector's first
+    // step will claim follows from the marks alone, so the host works its leading runs out (p3_first_step_runs)
+    // and hands them over with the launch.  Every workgroup starts on them at once instead of waiting 10 us for
+    // the first publication; the selector produces the same records in its first step, checks them against
+    // these, and ends the drain with an error if one differs.  That first step is a full one then (P3_BATCH_MAX
+    // slices: nobody is waiting for it, and the runs handed over should last until it is published).  0: none.
+    int32_t n_first;
+    P3FirstRun first_runs[P3_INLINE_RUNS];
 };
 
 #ifdef __cplusplus

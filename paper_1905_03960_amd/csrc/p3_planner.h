@@ -111,4 +111,49 @@ inline int64_t p3_planner_total_tiles(const P3PlanTables& t, int32_t tile) {
     return n;
 }
 
+// The leading runs of the first selection step of an iteration's first drain in SNAPSHOT mode under the
+// priority rule (Sec. 4.2: the most urgent ready slice first; all slices of a marked layer are ready at
+// once).  With `marks` the layers marked before the drain, the step claims the `step_slices` lowest-numbered
+// ready slices and groups them into runs the way the selector does: a slice continues the run of the slice
+// claimed just before it when that slice is its predecessor in the layer's memory.  Writes at most `cap` runs
+// (a prefix of the step's runs) and returns how many; 0 for an empty or invalid mark list.
+inline int32_t p3_first_step_runs(const P3PlanTables& t, const int32_t* marks, int32_t n_marks, int32_t step_slices,
+                                  P3FirstRun* out, int32_t cap) {
+    if (!marks || n_marks < 1 || step_slices < 1 || cap < 1) return 0;
+    std::vector<char> marked(static_cast<size_t>(t.L), 0);
+    for (int32_t i = 0; i < n_marks; ++i) {
+        const int32_t l = marks[i];
+        if (l < 0 || l >= t.L || marked[static_cast<size_t>(l)]) return 0;
+        marked[static_cast<size_t>(l)] = 1;
+    }
+    int64_t budget = step_slices;
+    int32_t n_runs = 0;
+    int64_t prev_g = -2, len = 0;
+    for (int32_t l = 0; l < t.L && budget > 0; ++l) {
+        if (!marked[static_cast<size_t>(l)]) continue;
+        const P3LayerDev& ly = t.layers[static_cast<size_t>(l)];
+        for (int32_t i = 0; i < ly.count && budget > 0; ++i, --budget) {
+            const int64_t g = static_cast<int64_t>(ly.first) + i;
+            const P3SliceDev& sl = t.slices[static_cast<size_t>(g)];
+            const bool head = !(prev_g + 1 == g && sl.index_in_layer > 0);
+            prev_g = g;
+            if (head) {
+                if (n_runs == cap) return n_runs;          // a prefix of the step is enough
+                out[n_runs].start = sl.start;
+                out[n_runs].layer = sl.layer;
+                len = 0;
+                n_runs += 1;
+            }
+            len += sl.len;
+            // the workers turn these records into addresses without looking at them again: nothing leaves here
+            // that is not inside the arena (and a run longer than the length field is left out)
+            if (sl.start < 0 || sl.len < 1 || sl.start > t.arena || sl.len > t.arena - sl.start ||
+                len > static_cast<int64_t>(UINT32_MAX))
+                return n_runs - 1;
+            out[n_runs - 1].len = static_cast<uint32_t>(len);
+        }
+    }
+    return n_runs;
+}
+
 #endif  // P3_PLANNER_H_

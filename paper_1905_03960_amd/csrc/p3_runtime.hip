@@ -59,6 +59,7 @@ struct p3_plan_s : P3PlanTables {
     int32_t watchdog_ms = 10000;
     int32_t persistent = 1;            // SNAPSHOT/TICKED: one fused launch (1) or selector + workers (0)
     int32_t lean = 0, next_lean = -1;  // 1: the build with small workgroups that share their compute unit
+    int32_t count_set = 0;             // which of the two sets of per-layer counts the current iteration uses
     // set by p3_set_mode / p3_set_tuning, applied by the next p3_begin_iter
     bool pending_mode = false, pending_tuning = false;
     int32_t next_mode = P3_MODE_SNAPSHOT;
@@ -408,8 +409,8 @@ int p3_bind(p3_plan_t* p, int32_t W, const void* const* grads, int32_t grad_dtyp
         dm(&p->d_layer_state, L);
         dm(&p->d_order, sizeof(int32_t) * K);
         dm(&p->d_epoch, sizeof(int32_t) * K);
-        dm(&p->d_layer_done, sizeof(unsigned long long) * L);
-        dm(&p->d_layer_req, sizeof(uint32_t) * L);
+        dm(&p->d_layer_done, sizeof(unsigned long long) * L * 2);     // two sets: iterations alternate (P3DrainArgs)
+        dm(&p->d_layer_req, sizeof(uint32_t) * L * 2);
         dm(&p->d_fifo, sizeof(int32_t) * L);
         dm(&p->d_t_seen, sizeof(uint64_t) * L);
         dm(&p->d_ctl, sizeof(P3Ctl));
@@ -443,8 +444,8 @@ int p3_bind(p3_plan_t* p, int32_t W, const void* const* grads, int32_t grad_dtyp
         if (e == hipSuccess) e = HIPC(hipMemcpy(p->d_ctl, &ctl, sizeof ctl, hipMemcpyHostToDevice));
         if (e == hipSuccess) e = HIPC(hipMemset(p->d_bitmap, 0, sizeof(unsigned long long) * n_words));
         if (e == hipSuccess) e = HIPC(hipMemset(p->d_layer_state, 0, L));
-        if (e == hipSuccess) e = HIPC(hipMemset(p->d_layer_done, 0, sizeof(unsigned long long) * L));
-        if (e == hipSuccess) e = HIPC(hipMemset(p->d_layer_req, 0, sizeof(uint32_t) * L));
+        if (e == hipSuccess) e = HIPC(hipMemset(p->d_layer_done, 0, sizeof(unsigned long long) * L * 2));
+        if (e == hipSuccess) e = HIPC(hipMemset(p->d_layer_req, 0, sizeof(uint32_t) * L * 2));
         if (e == hipSuccess) e = HIPC(hipMemset(p->d_order, 0xff, sizeof(int32_t) * K));
         if (e == hipSuccess) e = HIPC(hipMemset(p->d_epoch, 0, sizeof(int32_t) * K));
         if (e == hipSuccess) e = HIPC(hipDeviceSynchronize());
@@ -754,8 +755,12 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
     a.runq = p->d_runq;
     a.order = p->d_order;
     a.epoch = p->d_epoch;
-    a.layer_done = p->d_layer_done;
-    a.layer_req = p->d_layer_req;
+    // the iteration's first drain moves on to the set of counts that the iteration before it cleared
+    const int32_t count_set = p->first_drain ? (p->count_set ^ 1) : p->count_set;
+    a.layer_done = p->d_layer_done + static_cast<size_t>(count_set) * static_cast<size_t>(p->L);
+    a.layer_req = p->d_layer_req + static_cast<size_t>(count_set) * static_cast<size_t>(p->L);
+    a.layer_done_next = p->d_layer_done + static_cast<size_t>(count_set ^ 1) * static_cast<size_t>(p->L);
+    a.layer_req_next = p->d_layer_req + static_cast<size_t>(count_set ^ 1) * static_cast<size_t>(p->L);
     a.fifo = p->d_fifo;
     a.t_seen_dev = p->d_t_seen;
     a.ctl = p->d_ctl;
@@ -796,6 +801,12 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
             a.inline_marks[i] = static_cast<int32_t>(
                 p->mark_log[(p->drained_upto + static_cast<uint64_t>(i)) % p->mark_cap] & 0xffffffffull);
     }
+    // What the selector's first step will claim follows from these marks alone when nothing has been claimed yet
+    // and the rule is the paper's: its leading runs go along, so that no workgroup waits for the first publication.
+    a.n_first = 0;
+    if (a.n_inline > 0 && a.iter_begin && p->mode == P3_MODE_SNAPSHOT && p->policy == P3_POLICY_PRIORITY && p->persistent)
+        a.n_first = p3_first_step_runs(*p, a.inline_marks, a.n_inline, p->lean ? P3_BLOCK_LEAN : P3_BLOCK, a.first_runs,
+                                       P3_INLINE_RUNS);
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     ProfPair* pp = nullptr;
@@ -821,6 +832,7 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
     p->last_slot = slot;
     p->in_flight = true;
     p->first_drain = false;
+    p->count_set = count_set;
     p->drained_upto = limit;
     if (p->mode == P3_MODE_LIVE) p->live_issued = true;
     return P3_OK;
@@ -1254,6 +1266,7 @@ extern "C" int p3_drain_static(const p3_plan_t* p, int32_t W, const void* const*
         a.wd = wd;
         a.n_inline = n_ready;
         for (int32_t i = 0; i < n_ready; ++i) a.inline_marks[i] = ready_layers[i];
+        a.n_first = p3_first_step_runs(*p, a.inline_marks, a.n_inline, P3_BLOCK, a.first_runs, P3_INLINE_RUNS);
         P3GradPtrs gp;
         std::memset(&gp, 0, sizeof gp);
         for (int32_t k = 0; k < W; ++k) gp.p[k] = grads[k];

@@ -48,6 +48,14 @@ P3_HD int64_t p3_run_cells(int64_t start, int64_t len, int32_t tile_elems) {
     return (start + len - 1) / tile_elems - start / tile_elems + 1;
 }
 
+// How many slices the first selection step of a launch claims at most: enough to give every workgroup two
+// tiles, at least what one wavefront groups on its own, at most 256.  (The host works the first step of a
+// snapshot drain out ahead of the launch with the same rule; see P3FirstRun.)
+P3_HD int32_t p3_first_step_slices(uint32_t n_blocks, int32_t tiles_per_full_slice) {
+    int32_t cap = (2 * static_cast<int32_t>(n_blocks) + tiles_per_full_slice - 1) / tiles_per_full_slice;
+    return cap < 64 ? 64 : (cap > 256 ? 256 : cap);
+}
+
 // Is this record one the selector can have written for an arena of arena_elems elements and L layers?
 // Every address a worker derives from a record that passes lies inside [start, start+len), and that
 // inside the arena -- so a record read stale or torn ends the drain with an error instead of becoming

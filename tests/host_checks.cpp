@@ -89,6 +89,27 @@ int main() {
                 std::printf("l %d %d %lld %lld\n", t.layers[l].first, t.layers[l].count,
                             static_cast<long long>(t.layers[l].elems), static_cast<long long>(t.offset[l]));
             std::printf("tiles3328 %lld\n", static_cast<long long>(p3_planner_total_tiles(t, 3328)));
+        } else if (cmd == "first") {
+            // first <n_shards> <shard> <S> <step_slices> <cap> <L> sizes... <n_marks> marks...
+            long long n_shards, shard, S, step, cap, L, n_marks;
+            in >> n_shards >> shard >> S >> step >> cap >> L;
+            std::vector<int64_t> sizes = read_n<int64_t>(in, L > 0 ? static_cast<size_t>(L) : 0);
+            in >> n_marks;
+            std::vector<int32_t> marks = read_n<int32_t>(in, n_marks > 0 ? static_cast<size_t>(n_marks) : 0);
+            P3PlanTables t;
+            const int rc = p3_planner_build(sizes.data(), static_cast<int32_t>(L), S, static_cast<int32_t>(n_shards),
+                                            static_cast<int32_t>(shard), t);
+            if (rc != P3_OK) {
+                std::printf("first %d 0\n", rc);
+                continue;
+            }
+            std::vector<P3FirstRun> runs(static_cast<size_t>(cap > 0 ? cap : 1));   // exactly cap: an overrun is reported
+            const int32_t n = p3_first_step_runs(t, marks.data(), static_cast<int32_t>(n_marks), static_cast<int32_t>(step),
+                                                 runs.data(), static_cast<int32_t>(cap));
+            std::printf("first 0 %d\n", n);
+            for (int32_t r = 0; r < n; ++r)
+                std::printf("r %lld %u %d\n", static_cast<long long>(runs[static_cast<size_t>(r)].start),
+                            runs[static_cast<size_t>(r)].len, runs[static_cast<size_t>(r)].layer);
         } else if (cmd == "tiles") {
             long long start, len, layer, tile0, tile;
             in >> start >> len >> layer >> tile0 >> tile;

@@ -93,6 +93,43 @@ def test_planner_refuses_bad_input_under_sanitizers(driver):
     assert [ints(l)[0] for l in out] == [-1, -1, -1, -3, -3, -3, -3]
 
 
+def test_first_step_handed_over_with_a_launch_is_the_oracles_order_cut_into_runs(driver):
+    """The runs the host works out for the first selection step of a snapshot drain (they travel with the launch)
+    against the oracle: the first `step` slices of the oracle's snapshot order for the same marks, cut where the
+    layer changes or memory does not continue -- for random layer lists, mark subsets, step sizes and caps."""
+    rng = np.random.default_rng(77)
+    for case in range(120):
+        L = int(rng.integers(1, 30))
+        sizes = [int(max(1, round(10 ** rng.uniform(0, 5.3)))) for _ in range(L)]
+        S = int(rng.choice([1, 7, 1000, 4096, 50000, 1 << 20])) if sum(sizes) < 30000 else int(rng.choice([1000, 4096, 50000]))
+        step = int(rng.choice([1, 5, 64, 256, 832]))
+        cap = int(rng.choice([1, 3, 16, 128]))
+        marks = [int(x) for x in rng.permutation(L)[:int(rng.integers(1, L + 1))]]
+        out = driver([f"first 1 0 {S} {step} {cap} {L} " + " ".join(map(str, sizes)) + f" {len(marks)} " +
+                      " ".join(map(str, marks))])
+        rc, n = ints(out[0])
+        got = [tuple(ints(l)) for l in out[1:1 + n]]
+        o = OraclePlan(sizes, S)
+        layer, off, ln = o.slice_table()
+        base = np.zeros(L, dtype=np.int64)              # the library's arena offsets: layers padded to 64 elements
+        for l in range(1, L):
+            base[l] = base[l - 1] + (sizes[l - 1] + 63) // 64 * 64
+        order = o.order_snapshot(marks + [-1])[:step]
+        want = []
+        for i, g in enumerate(order):
+            start = int(base[layer[g]] + off[g])
+            if i > 0 and order[i - 1] + 1 == g and layer[g - 1] == layer[g]:
+                want[-1][1] += int(ln[g])
+            else:
+                want.append([start, int(ln[g]), int(layer[g])])
+        want = [tuple(w) for w in want][:cap]
+        assert rc == 0 and got == want, (case, sizes, S, step, cap, marks, got[:4], want[:4])
+    # nothing is handed over for an empty, a repeated or an unknown mark
+    for bad in ("0", "2 1 1", "1 7"):
+        out = driver([f"first 1 0 10 64 8 3 5 50 500 {bad}"])
+        assert ints(out[0]) == [0, 0]
+
+
 # ----------------------------------------------------------- tile arithmetic ----
 def test_tiles_partition_their_run(driver):
     """Tiles of a run, in tile-number order, are consecutive, non-empty, cover the run exactly, lie within one
