@@ -31,8 +31,8 @@ HBM_PEAK_GBPS = 8000.0
 # profiles/p3_drain_kernel_*_hbm_traffic.md (already scaled by what the counters read for a plain copy), valid
 # for the kernel sources whose hash is given, the workload's default slice size and the default launch shape.
 TRAFFIC = {
-    "sources_sha256": "dd03bbbf45b828f5fa9894f8fe1e7806d23e1d076e659e8efc296e7de103ba95",
-    "bytes_per_launch": {"vgg19": 6902781247, "vgg19_bf16": 6902781205},
+    "sources_sha256": "f815b462532358ef1dae0bf15804cd77f041c841a9d17fb916d926889c35afc3",
+    "bytes_per_launch": {"vgg19": 6902033462, "vgg19_bf16": 6902039235},
 }
 
 
