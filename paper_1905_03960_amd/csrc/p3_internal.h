@@ -182,8 +182,8 @@ struct P3DrainArgs {
     // (else n_inline = 0 and the kernel reads the pinned mark log over the host link)
     int32_t n_inline;
     int32_t inline_marks[P3_INLINE_MARKS];
-    // The first drain of an iteration in SNAPSHOT mode under the priority rule: what the selector's first
-    // step will claim follows from the marks alone, so the host works its leading runs out (p3_first_step_runs)
+    // A drain in SNAPSHOT mode under the priority rule: what the selector's first step will claim follows
+    // from the drain's marks alone, so the host works its leading runs out (p3_first_step_runs)
     // and hands them over with the launch.  Every workgroup starts on them at once instead of waiting 10 us for
     // the first publication; the selector produces the same records in its first step, checks them against
     // these, and ends the drain with an error if one differs.  That first step is a full one then (P3_BATCH_MAX

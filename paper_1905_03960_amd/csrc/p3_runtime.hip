@@ -801,10 +801,15 @@ int p3_drain(p3_plan_t* p, void* hip_stream) {
             a.inline_marks[i] = static_cast<int32_t>(
                 p->mark_log[(p->drained_upto + static_cast<uint64_t>(i)) % p->mark_cap] & 0xffffffffull);
     }
-    // What the selector's first step will claim follows from these marks alone when nothing has been claimed yet
-    // and the rule is the paper's: its leading runs go along, so that no workgroup waits for the first publication.
+    // What the selector's first step will claim follows from these marks alone when the rule is the paper's:
+    // every earlier drain of the iteration has claimed all that was ready to it (a SNAPSHOT drain ends when
+    // nothing ready is left), so the lowest-numbered slices of the newly marked layers come next.  Their leading
+    // runs go along with the launch, so that no workgroup waits for the first publication.  (Not after an abort:
+    // the drain it stopped may have left ready slices behind.  One cut short by its watchdog would be noticed by
+    // the selector's comparison and reported as an error.)
     a.n_first = 0;
-    if (a.n_inline > 0 && a.iter_begin && p->mode == P3_MODE_SNAPSHOT && p->policy == P3_POLICY_PRIORITY && p->persistent)
+    const bool aborted = reinterpret_cast<std::atomic<uint32_t>*>(&p->hs->abort_flag)->load(std::memory_order_acquire) != 0u;
+    if (a.n_inline > 0 && !aborted && p->mode == P3_MODE_SNAPSHOT && p->policy == P3_POLICY_PRIORITY && p->persistent)
         a.n_first = p3_first_step_runs(*p, a.inline_marks, a.n_inline, p->lean ? P3_BLOCK_LEAN : P3_BLOCK, a.first_runs,
                                        P3_INLINE_RUNS);
 
