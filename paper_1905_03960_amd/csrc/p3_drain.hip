@@ -1689,6 +1689,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
 
     // The first round is a DRAIN round with nothing to drain: it finds the tile of the first number.
     if (wave == 0) {
+        const uint32_t k_first = take_ticket(ctl, lane);      // asked for now, looked at below
         if (WAIT && a.n_first > 0) {
             // the leading runs of the first selection step came with the launch: they go into the ring as if
             // they had been read from the queue (their tile numbers follow from their order), and the
@@ -1723,7 +1724,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
             r_have = static_cast<uint32_t>(a.n_first);
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");      // the ring is read by other lanes
         }
-        k_wait = uni(take_ticket(ctl, lane));
+        k_wait = uni(k_first);
         P3TileDesc d0;
         d0.start = 0;
         d0.n = P3T_DRAIN;
@@ -1863,7 +1864,9 @@ __global__ void __launch_bounds__(P3_BLOCK) P3_KERNEL_ATTR p3_drain_kernel(const
     __shared__ SelectorLds lds;
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
-    if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), blockIdx.x != 0);
+    // (nobody waits for the registration here: the worker's first round waits for everything its leader has
+    // outstanding -- registration, first tile number, the runs handed over -- in one go, long before its first store)
+    if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), false);
     if (blockIdx.x == 0) run_selector(a, lds);
     run_worker<WT, BF16, WD, true>(a, gp, s_desc, s_runs);
 }
