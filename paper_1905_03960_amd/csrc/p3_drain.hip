@@ -1578,17 +1578,37 @@ __device__ __attribute__((noinline)) Located locate_run(QueueCtx a, FlushCtx fc,
 // that share one condition on both sides of the loop's back edge the compiler
 // may give the other lanes a private loop around the barriers that the leader
 // lane never re-enters: the workgroup then spins on a stale descriptor forever.)
+// What the out-of-line helpers of the worker loop need.  It lives in LDS, not in scalar registers: the helpers are
+// called once in a while (a refill, a completed layer, a write-back round), the loop around them every few
+// microseconds, and twenty-six scalar registers held for them were spilled and moved about in every round.
+struct WorkerCtx {
+    FlushCtx fc;
+    QueueCtx qc;
+};
+__device__ __forceinline__ FlushCtx flush_ctx(const WorkerCtx& c) {
+    asm volatile("" ::: "memory");             // read where it is used, not once in front of the loop
+    return c.fc;
+}
+__device__ __forceinline__ QueueCtx queue_ctx(const WorkerCtx& c) {
+    asm volatile("" ::: "memory");
+    return c.qc;
+}
+
 template <int WT, bool BF16, bool WD, bool WAIT>
 __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtrs& gp, P3TileDesc& s_desc,
-                                           P3Run* s_runs) {
+                                           P3Run* s_runs, WorkerCtx& s_ctx) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: whole wavefronts branch on it
     P3Ctl* ctl = a.ctl;
     const HyperT<WD> h = {a.lr, a.mu, a.rescale, a.wd};
     const uint64_t t_enter = clock_now();
-    const QueueCtx qc = {a.ctl, a.runq, a.hs, a.watchdog_ticks, a.arena_elems, a.L, a.tile_elems};
-    const FlushCtx fc = {a.ctl, a.layer_req, a.t_seen_dev, a.t_seen, a.t_done, a.done_flag, a.iter_seq, a.L};
+    if (tid == 0) {
+        const QueueCtx qc0 = {a.ctl, a.runq, a.hs, a.watchdog_ticks, a.arena_elems, a.L, a.tile_elems};
+        const FlushCtx fc0 = {a.ctl, a.layer_req, a.t_seen_dev, a.t_seen, a.t_done, a.done_flag, a.iter_seq, a.L};
+        s_ctx.qc = qc0;
+        s_ctx.fc = fc0;
+    }
     const int xcd = xcd_of_this_wave();
 
     // leader state (wavefront 0 only), scalar
@@ -1614,16 +1634,16 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
         if (po_cnt_a != 0u) {
             const unsigned long long old = uni(po_old_a);
             if (old + static_cast<unsigned long long>(po_cnt_a) == uni(po_le_a)) {
-                if (old == 0ull && po_layer_a == 0) complete_alone(fc, po_layer_a, lane);
-                else complete_layer(fc, po_layer_a, xcd, lane);
+                if (old == 0ull && po_layer_a == 0) complete_alone(flush_ctx(s_ctx), po_layer_a, lane);
+                else complete_layer(flush_ctx(s_ctx), po_layer_a, xcd, lane);
             }
             po_cnt_a = 0u;
         }
         if (po_cnt_b != 0u) {
             const unsigned long long old = uni(po_old_b);
             if (old + static_cast<unsigned long long>(po_cnt_b) == uni(po_le_b)) {
-                if (old == 0ull && po_layer_b == 0) complete_alone(fc, po_layer_b, lane);
-                else complete_layer(fc, po_layer_b, xcd, lane);
+                if (old == 0ull && po_layer_b == 0) complete_alone(flush_ctx(s_ctx), po_layer_b, lane);
+                else complete_layer(flush_ctx(s_ctx), po_layer_b, xcd, lane);
             }
             po_cnt_b = 0u;
         }
@@ -1748,7 +1768,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
                 count_tile(prev_layer, prev_n, prev_long, true);
                 prev_n = 0;
                 settle();
-                const Located f = locate_run<WAIT>(qc, fc, xcd, s_runs, k_wait, r_next, r_have, t_enter, lane, true);
+                const Located f = locate_run<WAIT>(queue_ctx(s_ctx), flush_ctx(s_ctx), xcd, s_runs, k_wait, r_next, r_have, t_enter, lane, true);
                 r_next = uni(f.r_next);
                 r_have = uni(f.r_have);
                 P3TileDesc dn;
@@ -1799,7 +1819,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
                 prev_n = 0;
                 settle();
             }
-            if (flush_due(fv, false)) serve_flush(fc, fv.req, xcd, lane);
+            if (flush_due(fv, false)) serve_flush(flush_ctx(s_ctx), fv.req, xcd, lane);
 
             P3TileDesc dn;
             dn.start = 0;
@@ -1834,7 +1854,7 @@ __device__ __forceinline__ void run_worker(const P3DrainArgs& a, const P3GradPtr
     }
 
     // (the loop ends behind a DRAIN round: nothing uncounted, nothing unlooked-at)
-    if (wave == 0) leave_loop(fc, xcd, lane);
+    if (wave == 0) leave_loop(flush_ctx(s_ctx), xcd, lane);
 
     // Last workgroup out re-arms the per-launch words for the next drain.
     if (lane_is(tid, 0)) {
@@ -1864,11 +1884,12 @@ __global__ void __launch_bounds__(P3_BLOCK) P3_KERNEL_ATTR p3_drain_kernel(const
     __shared__ SelectorLds lds;
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
+    __shared__ WorkerCtx s_ctx;
     // (nobody waits for the registration here: the worker's first round waits for everything its leader has
     // outstanding -- registration, first tile number, the runs handed over -- in one go, long before its first store)
     if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), false);
     if (blockIdx.x == 0) run_selector(a, lds);
-    run_worker<WT, BF16, WD, true>(a, gp, s_desc, s_runs);
+    run_worker<WT, BF16, WD, true>(a, gp, s_desc, s_runs, s_ctx);
 }
 
 // Two launches on one stream: the selector alone (one workgroup) ...
@@ -1882,8 +1903,9 @@ template <int WT, bool BF16, bool WD>
 __global__ void __launch_bounds__(P3_BLOCK) P3_KERNEL_ATTR p3_work_kernel(const P3DrainArgs a, const P3GradPtrs gp) {
     __shared__ P3TileDesc s_desc;
     __shared__ P3Run s_runs[P3_RUN_CACHE];
+    __shared__ WorkerCtx s_ctx;
     if (threadIdx.x < 64) enter_xcd(a.ctl, xcd_of_this_wave(), static_cast<int>(threadIdx.x), true);
-    run_worker<WT, BF16, WD, false>(a, gp, s_desc, s_runs);
+    run_worker<WT, BF16, WD, false>(a, gp, s_desc, s_runs, s_ctx);
 }
 
 // ---------------------------------------------------------------- launcher ----
