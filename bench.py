@@ -31,8 +31,8 @@ HBM_PEAK_GBPS = 8000.0
 # profiles/p3_drain_kernel_*_hbm_traffic.md (already scaled by what the counters read for a plain copy), valid
 # for the kernel sources whose hash is given, the workload's default slice size and the default launch shape.
 TRAFFIC = {
-    "sources_sha256": "a10af57f6d91e0781e8de8a202eaceda7d002e8aaaeb452e47ceedd8993a21af",
-    "bytes_per_launch": {"vgg19": 6902011462, "vgg19_bf16": 6902064331},
+    "sources_sha256": "b624c4f9fec65e35dbe75ef78c1adb867aefcce31b194f9b3ba1f2da87426b7f",
+    "bytes_per_launch": {"vgg19": 6901984589, "vgg19_bf16": 6902046605},
 }
 
 
